@@ -1,0 +1,416 @@
+"""Pins for the CPU oracle: closed forms, invariants, brute force, planted solutions.
+
+None of these tests needs a GPU.  Each pins a part of oracle/conqur_oracle.c to
+something other than itself: values the paper states, textbook closed forms,
+library routines (numpy SVD, torch bf16 conversion), brute force on tiny inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2605_10793_amd import inputs as I
+
+
+def hadamard(d):
+    h = np.array([[1.0]])
+    while h.shape[0] < d:
+        h = np.block([[h, h], [h, -h]])
+    return h
+
+
+def gauss(shape, seed):
+    return np.random.Generator(np.random.Philox(key=seed)).standard_normal(shape)
+
+
+# --------------------------------------------------------------------------- rounding
+
+def test_bf16_rounding_matches_library_conversion():
+    g = np.random.Generator(np.random.Philox(key=11))
+    x = (g.standard_normal(20000) * np.exp(8 * g.standard_normal(20000))).astype(np.float32)
+    # exact ties: bf16 value + half an ulp
+    base = I.round_to_bf16(x[:2000])
+    ties = (base.view(np.uint32) | np.uint32(0x8000)).view(np.float32)
+    x = np.concatenate([x, ties, np.array([0.0, -0.0, 1.0, -1.0, 3.0e38, 1e-30], np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([O.round_bf16(float(v)) for v in x], dtype=np.float32)
+    assert np.array_equal(got, want)
+    assert np.array_equal(O.round_operand(x, "bf16"), want)
+    assert np.array_equal(O.round_operand(x, "f32"), x)
+
+
+# --------------------------------------------------------------------------- step: brute force
+
+@pytest.mark.parametrize("d,T,seed", [(2, 5, 1), (4, 9, 2), (8, 16, 3)])
+def test_step_batch_brute_force_tiny(d, T, seed):
+    """Eq. 1-2 evaluated with python loops on tiny inputs."""
+    X = gauss((T, d), seed).astype(np.float32)
+    R = I.random_orthogonal(d, seed).astype(np.float32)
+    oc = O.OracleCalibrator(d, 1, "f32", R)
+    Y, S = oc.step_batch(X, True, True)
+    M = [[0.0] * d for _ in range(d)]
+    obj = 0.0
+    for i in range(T):
+        nrm = math.sqrt(sum(float(X[i, k]) ** 2 for k in range(d)))
+        xt = [float(X[i, k]) / nrm for k in range(d)]
+        y = [sum(xt[k] * float(R[k, j]) for k in range(d)) for j in range(d)]
+        z = [(1.0 if y[j] >= 0 else -1.0) / math.sqrt(d) for j in range(d)]
+        obj += sum((y[j] - z[j]) ** 2 for j in range(d))
+        for k in range(d):
+            for j in range(d):
+                M[k][j] += xt[k] * z[j]
+        for j in range(d):
+            assert S[i, j] == (1 if y[j] >= 0 else -1)
+            assert abs(Y[i, j] - y[j] * nrm) < 1e-12 * max(1.0, nrm)
+    assert np.allclose(oc.M[0], np.array(M), rtol=0, atol=1e-13)
+    # the l1 identity assumes ||y~|| = 1; the fp32 rotation is orthogonal to ~1e-7
+    assert abs(oc.objective()[0] - obj) < 2e-6 * T
+    assert oc.n[0] == T and oc.skipped[0] == 0
+
+
+def test_sign_of_zero_is_plus_one():
+    # x = e_0 with R = I gives y = (1, 0, 0, 0); zeros (and -0.0) must map to +1
+    X = np.array([[1.0, 0.0, -0.0, 0.0], [0.0, -2.0, 0.0, -0.0]], dtype=np.float32)
+    oc = O.OracleCalibrator(4, 1, "f32", np.eye(4, dtype=np.float32))
+    _, S = oc.step_batch(X, False, True)
+    assert S.tolist() == [[1, 1, 1, 1], [1, -1, 1, 1]]
+    want = (np.outer([1, 0, 0, 0], [1, 1, 1, 1]) + np.outer([0, -1, 0, 0], [1, -1, 1, 1])) / 2.0
+    assert np.allclose(oc.M[0], want, atol=1e-15)
+
+
+def test_zero_and_nonfinite_rows_are_skipped():
+    X = gauss((6, 8), 5).astype(np.float32)
+    X[1] = 0.0
+    X[4, 3] = np.inf
+    X[5, 0] = np.nan
+    R = I.random_orthogonal(8, 6).astype(np.float32)
+    a = O.OracleCalibrator(8, 1, "f32", R)
+    _, S = a.step_batch(X, False, True)
+    b = O.OracleCalibrator(8, 1, "f32", R)
+    b.step_batch(X[[0, 2, 3]])
+    assert a.n[0] == 3 and a.skipped[0] == 3
+    assert np.array_equal(a.M, b.M) and a.L[0] == b.L[0]
+    assert not S[1].any() and not S[4].any() and not S[5].any()
+
+
+# --------------------------------------------------------------------------- step: closed forms
+
+@pytest.mark.parametrize("d,T", [(16, 64), (64, 300)])
+def test_prealigned_corners(d, T):
+    """Rows a_i * c_i * R*^T with R = R*: y is exactly a scaled corner.
+
+    Then the signs are the planted corner, the objective is zero, M = R* (C^T C) / d^(3/2)...
+    and the Procrustes update returns the planted rotation."""
+    g = np.random.Generator(np.random.Philox(key=d))
+    Rs = I.random_orthogonal(d, 21)
+    C = np.where(g.random((T, d)) < 0.5, -1.0, 1.0)
+    a = np.exp(g.standard_normal(T))
+    X = (a[:, None] * C / math.sqrt(d)) @ Rs.T
+    oc = O.OracleCalibrator(d, 1, "f32", Rs.astype(np.float32))
+    Xf = X.astype(np.float32)
+    Y, S = oc.step_batch(Xf, True, True)
+    margin = np.abs(Y).min()
+    assert margin > 1e-3 * a.min() / math.sqrt(d)      # fp32 input rounding cannot flip a sign
+    assert np.array_equal(S, C.astype(np.int8))
+    assert abs(oc.objective()[0]) < 1e-4 * T            # zero up to fp32 rounding of X and R
+    want_M = Rs @ (C.T @ C) / d                          # xn_i = c_i R*^T / sqrt(d), corner c_i / sqrt(d)
+    assert np.linalg.norm(oc.M[0] - want_M) < 1e-5 * np.linalg.norm(want_M)
+    st = oc.update_rotation()[0]
+    assert np.abs(oc.R[0] - Rs).max() < 1e-5
+    assert st["orth_err"] < 1e-10
+
+
+def test_one_hot_rows_under_hadamard():
+    """x = s * e_k and R = H / sqrt(d): every rotated row is a corner, ||y~||_1 = sqrt(d)."""
+    d = 32
+    H = hadamard(d)
+    X = np.zeros((d, d), dtype=np.float32)
+    for k in range(d):
+        X[k, k] = (-1.0) ** k * (k + 1)
+    oc = O.OracleCalibrator(d, 1, "f32", (H / math.sqrt(d)).astype(np.float32))
+    _, S = oc.step_batch(X, False, True)
+    assert abs(oc.L[0] - d * math.sqrt(d)) < 1e-5
+    assert abs(oc.objective()[0]) < 1e-5
+    signs_x = np.sign(np.diag(X))[:, None]
+    assert np.array_equal(S, (signs_x * H).astype(np.int8))
+    # M = sum_k sign_k e_k^T (sign_k h_k) / sqrt(d) = H / sqrt(d)
+    assert np.allclose(oc.M[0], H / math.sqrt(d), atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_trace_identity_and_l1_identity(dtype):
+    """<R_op, M> = L / sqrt(d), and Eq. 1 summed directly equals 2n - 2L/sqrt(d).
+
+    The second identity needs ||y~|| = 1, i.e. an orthogonal operand, so it is
+    checked with the fp32 operand; the first holds for any operand."""
+    w = I.small_workload(48, 200, dtype=dtype, seed=9)
+    X = I.batch(w, 0)
+    R = I.initial_rotation(w)
+    oc = O.OracleCalibrator(48, 1, dtype, R)
+    Y, S = oc.step_batch(X, True, True)
+    Rop = oc.R_op[0].astype(np.float64)
+    assert abs((Rop * oc.M[0]).sum() - oc.L[0] / math.sqrt(48)) < 1e-10 * oc.L[0]
+    nrm = np.linalg.norm(X.astype(np.float64), axis=1, keepdims=True)
+    direct = (((Y / nrm) - S / math.sqrt(48)) ** 2).sum()
+    tol = 1e-5 if dtype == "f32" else 2e-2   # bf16 operand is orthogonal only to ~2^-9
+    assert abs(direct - oc.objective()[0]) < tol * 200
+    assert 0.0 <= oc.objective()[0] <= 2.0 * 200
+    assert oc.L[0] <= 200 * math.sqrt(48) * (1 + 1e-2)
+
+
+def test_per_head_equals_independent_blocks():
+    w = I.small_workload(64, 50, heads=4, seed=13)
+    X = I.batch(w, 0)
+    R0 = I.initial_rotation(w)
+    full = O.OracleCalibrator(64, 4, "bf16", R0)
+    full.step_batch(X)
+    for h in range(4):
+        one = O.OracleCalibrator(16, 1, "bf16", R0[h])
+        one.step_batch(np.ascontiguousarray(X[:, 16 * h:16 * (h + 1)]))
+        assert np.array_equal(one.M[0], full.M[h]) and one.L[0] == full.L[h]
+    assert np.allclose(full.objective(), 2 * 50 - 2 * full.L / 4.0)
+
+
+def test_strided_rows():
+    X = gauss((10, 24), 3).astype(np.float32)
+    R = I.random_orthogonal(16, 4).astype(np.float32)
+    a = O.OracleCalibrator(16, 1, "f32", R); a.step_batch(X)               # stride 24, d 16
+    b = O.OracleCalibrator(16, 1, "f32", R); b.step_batch(np.ascontiguousarray(X[:, :16]))
+    assert np.array_equal(a.M, b.M)
+
+
+# --------------------------------------------------------------------------- SVD / Procrustes
+
+@pytest.mark.parametrize("d", [1, 2, 3, 7, 32, 65])
+def test_jacobi_svd_against_library(d):
+    A = gauss((d, d), 100 + d) * np.exp(2 * gauss((1, d), 200 + d))
+    U, s, V, _ = O.jacobi_svd(A)
+    assert np.allclose((U * s) @ V.T, A, atol=1e-12 * np.abs(A).max() * d)
+    assert np.allclose(U.T @ U, np.eye(d), atol=1e-12)
+    assert np.allclose(V.T @ V, np.eye(d), atol=1e-12)
+    assert np.allclose(np.sort(s)[::-1], np.linalg.svd(A, compute_uv=False), rtol=1e-11, atol=1e-13)
+
+
+def test_jacobi_svd_special_matrices():
+    D = np.diag([3.0, -2.0, 0.5, 1e-6])
+    U, s, V, _ = O.jacobi_svd(D)
+    assert np.allclose(np.sort(s), [1e-6, 0.5, 2.0, 3.0])
+    assert np.allclose(U @ V.T, np.diag([1.0, -1.0, 1.0, 1.0]), atol=1e-14)   # polar of a diagonal matrix
+    Q = I.random_orthogonal(12, 3)
+    U, s, V, _ = O.jacobi_svd(Q)
+    assert np.allclose(s, 1.0) and np.allclose(U @ V.T, Q, atol=1e-13)
+    u = gauss((9,), 1); v = gauss((9,), 2)
+    U, s, V, _ = O.jacobi_svd(np.outer(u, v))
+    assert np.isclose(s.max(), np.linalg.norm(u) * np.linalg.norm(v)) and (s > 1e-12).sum() == 1
+    assert np.allclose(U.T @ U, np.eye(9), atol=1e-12)                          # completed basis
+    U, s, V, _ = O.jacobi_svd(np.zeros((5, 5)))
+    assert np.allclose(U.T @ U, np.eye(5)) and not s.any()
+
+
+def test_procrustes_2x2_closed_form():
+    g = np.random.Generator(np.random.Philox(key=77))
+    for _ in range(50):
+        M = g.standard_normal((2, 2))
+        if np.linalg.det(M) <= 0.05:
+            continue
+        th = math.atan2(M[1, 0] - M[0, 1], M[0, 0] + M[1, 1])
+        want = np.array([[math.cos(th), -math.sin(th)], [math.sin(th), math.cos(th)]])
+        R, st = O.procrustes(M)
+        assert np.allclose(R, want, atol=1e-12)
+    M = np.array([[1.0, 0.2], [0.1, -2.0]])                   # det < 0: optimum is a reflection
+    R, st = O.procrustes(M)
+    assert np.isclose(np.linalg.det(R), -1.0)
+    assert np.isclose(st["inner"], np.linalg.svd(M, compute_uv=False).sum())
+
+
+@pytest.mark.parametrize("d,cond", [(8, 10.0), (64, 1e3), (128, 1e7)])
+def test_planted_polar_factor(d, cond):
+    """A = Q P with P symmetric positive definite: polar(A) = Q in closed form."""
+    Q = I.random_orthogonal(d, 31)
+    sig = np.logspace(0, -math.log10(cond), d)
+    P, _ = I.spd_with_spectrum(d, sig, 32)
+    R, st = O.procrustes(Q @ P)
+    assert np.abs(R - Q).max() < 1e-9 * cond ** 0.5
+    assert np.isclose(st["nuclear"], sig.sum(), rtol=1e-10)
+    assert np.isclose(st["inner"], sig.sum(), rtol=1e-10)
+
+
+def test_procrustes_beats_random_orthogonal_perturbations():
+    d = 8
+    w = I.small_workload(d, 100, seed=5)
+    oc = O.OracleCalibrator(d, 1, "f32", I.initial_rotation(w))
+    oc.step_batch(I.batch(w, 0))
+    M = oc.M[0].copy()
+    R, st = O.procrustes(M)
+    best = (R * M).sum()
+    assert np.isclose(best, np.linalg.svd(M, compute_uv=False).sum(), rtol=1e-12)
+    g = np.random.Generator(np.random.Philox(key=99))
+    for t in range(1000):
+        eps = [1e-4, 1e-2, 0.3, 3.0][t % 4]
+        K = g.standard_normal((d, d)) * eps
+        K = K - K.T
+        Qn = np.linalg.solve(np.eye(d) + K, np.eye(d) - K)       # Cayley transform: orthogonal, near I
+        cand = R @ Qn if t % 8 < 4 else I.random_orthogonal(d, 1000 + t)
+        assert np.allclose(cand.T @ cand, np.eye(d), atol=1e-10)
+        assert (cand * M).sum() <= best + 1e-10 * abs(best)
+
+
+def test_rank_deficient_update_is_orthogonal_and_optimal():
+    d, T = 24, 10
+    w = I.small_workload(d, T, seed=15)
+    oc = O.OracleCalibrator(d, 1, "bf16", I.initial_rotation(w))
+    oc.step_batch(I.batch(w, 0))
+    M = oc.M[0].copy()
+    assert np.linalg.matrix_rank(M) <= T
+    R, st = O.procrustes(M)
+    assert st["orth_err"] < 1e-12
+    assert np.isclose(st["inner"], np.linalg.svd(M, compute_uv=False).sum(), rtol=1e-12)
+
+
+def test_proximal_reading_limits():
+    """lambda -> 0+ keeps <R, M> maximal and stays closest to R_prev; on a nonsingular M it is the paper's update."""
+    d, T = 16, 6
+    w = I.small_workload(d, T, seed=16)
+    R0 = I.initial_rotation(w)[0].astype(np.float64)
+    oc = O.OracleCalibrator(d, 1, "bf16", R0)
+    oc.step_batch(I.batch(w, 0))
+    M = oc.M[0].copy()
+    nuc = np.linalg.svd(M, compute_uv=False).sum()
+    R_free, _ = O.procrustes(M)
+    R_prox, st = O.procrustes(M, R0, 1e-6)
+    assert st["orth_err"] < 1e-12
+    assert (R_prox * M).sum() > nuc * (1 - 1e-5)
+    assert np.linalg.norm(R_prox - R0) <= np.linalg.norm(R_free - R0) + 1e-9
+    # with lambda > 0 the update is polar(M + lambda tau R_prev): check against the library SVD
+    lam = 0.1
+    tau = np.linalg.norm(M) / math.sqrt(d)
+    U, _, Vt = np.linalg.svd(M + lam * tau * R0)
+    R_l, st = O.procrustes(M, R0, lam)
+    assert np.allclose(R_l, U @ Vt, atol=1e-10) and np.isclose(st["tau"], tau)
+    # nonsingular M: tiny lambda changes nothing
+    Mfull = gauss((d, d), 8)
+    assert np.allclose(O.procrustes(Mfull)[0], O.procrustes(Mfull, R0, 1e-12)[0], atol=1e-9)
+
+
+def test_update_does_not_increase_objective_on_fixed_batch():
+    """Alternating scheme (Sec. 3.3): re-scoring the same rows after the update cannot be worse."""
+    w = I.small_workload(32, 400, seed=17, dtype="f32")
+    X = I.batch(w, 0)
+    oc = O.OracleCalibrator(32, 1, "f32", I.initial_rotation(w))
+    prev = None
+    for _ in range(4):
+        oc.step_batch(X)
+        obj = oc.objective()[0]
+        if prev is not None:
+            assert obj <= prev + 1e-6
+        prev = obj
+        oc.update_rotation()
+        assert oc.n[0] == 0 and not oc.M.any() and oc.L[0] == 0.0   # statistics are cleared per update
+
+
+def test_transposed_convention_matches_section_3():
+    """Sec. 3.3 writes C = Z^T X~ and R <- U V^T acting on columns; the row convention is its transpose."""
+    w = I.small_workload(12, 80, seed=18, dtype="f32")
+    X = I.batch(w, 0).astype(np.float64)
+    R0 = I.initial_rotation(w)[0].astype(np.float64)
+    oc = O.OracleCalibrator(12, 1, "f32", R0)
+    oc.step_batch(X.astype(np.float32))
+    Xt = X / np.linalg.norm(X, axis=1, keepdims=True)
+    Rcol = R0.T                                              # Sec. 3: y = R x
+    Z = np.where(Xt @ Rcol.T >= 0, 1.0, -1.0) / math.sqrt(12)
+    Cpaper = Z.T @ Xt
+    assert np.allclose(oc.M[0], Cpaper.T, atol=1e-12)
+    U, _, Vt = np.linalg.svd(Cpaper)
+    oc.update_rotation()
+    assert np.allclose(oc.R[0], (U @ Vt).T, atol=1e-6)
+
+
+# --------------------------------------------------------------------------- quantiser
+
+def test_quantiser_zero_error_cases(golden):
+    d = 64
+    levels = int(golden["sym_levels_b4"])
+    assert levels == 7
+    g = np.random.Generator(np.random.Philox(key=5))
+    corners = np.where(g.random((10, d)) < 0.5, -1.0, 1.0) * np.exp(g.standard_normal((10, 1)))
+    poles = np.zeros((4, d)); poles[np.arange(4), [0, 5, 9, 63]] = [1.0, -2.0, 3.5, -0.25]
+    grid = g.integers(-levels, levels + 1, size=(6, d)).astype(np.float64)
+    grid[:, 0] = levels                                        # the row max sits on the top level
+    X = I.round_to_bf16(np.concatenate([corners, poles, grid * 0.125, np.zeros((2, d))]).astype(np.float32))
+    oc = O.OracleCalibrator(d, 1, "bf16", np.eye(d, dtype=np.float32))
+    sse, en, rows, codes = oc.quant_error(X, 4, True, True)
+    # zero up to the fp32 rounding of the scale D = max / 7 (relative 2^-24, squared)
+    assert sse <= 1e-13 * en and not rows[14:].any()
+    assert np.isclose(en, (X.astype(np.float64) ** 2).sum())
+    assert np.array_equal(np.abs(codes[:10]), np.full((10, d), 7))
+    assert np.array_equal(codes[14:20], grid.astype(np.int8))
+
+
+def test_quantiser_hand_computed_rows():
+    # row max 7 -> D = 1; entries k + 1/4 round to k with error 1/4; 2.5 and 3.5 are ties -> even
+    row = np.array([7.0, 0.25, 1.25, -2.25, 2.5, 3.5, -6.75, 0.0], dtype=np.float32)
+    want_codes = [7, 0, 1, -2, 2, 4, -7, 0]
+    want_sse = 3 * 0.0625 + 0.25 + 0.25 + 0.0625
+    oc = O.OracleCalibrator(8, 1, "f32", np.eye(8, dtype=np.float32))
+    sse, en, rows, codes = oc.quant_error(row[None, :], 4, True, True)
+    assert codes[0].tolist() == want_codes
+    assert np.isclose(sse, want_sse, rtol=1e-12) and np.isclose(en, (row.astype(np.float64) ** 2).sum())
+    # 8-bit: D = 7/127
+    sse8, _, _, c8 = oc.quant_error(row[None, :], 8, False, True)
+    assert c8[0, 0] == 127 and sse8 < sse / 100
+
+
+def test_quantiser_bounds_from_appendix_b(golden):
+    """||Q(y)-y||^2 <= d D^2 / 4 per row; <= 1/(4*49) for unit corners' neighbourhood, <= d/(4*49) in general."""
+    d = 256
+    w = I.small_workload(d, 300, seed=19)
+    X = I.batch(w, 0)
+    R = I.initial_rotation(w)
+    oc = O.OracleCalibrator(d, 1, "bf16", R)
+    sse, en, rows, _ = oc.quant_error(X, 4, True, False)
+    Y = I.round_to_bf16((X.astype(np.float64) @ oc.R_op[0].astype(np.float64)).astype(np.float32)).astype(np.float64)
+    delta = np.abs(Y).max(axis=1) / golden["sym_levels_b4"]
+    assert np.all(rows <= d * delta ** 2 / 4 * (1 + 1e-6))
+    rho = np.abs(Y).max(axis=1) ** 2 / (Y ** 2).sum(axis=1)
+    assert np.all(rho >= 1.0 / d - 1e-12) and np.all(rho <= 1.0)
+    # uniform-noise expectation d D^2 / 12 on dense rows (statistical, loose)
+    assert 0.5 < rows.sum() / (d * delta ** 2 / 12).sum() < 1.2
+    # worked number of App. B: range of a sign-mixed corner at d = 4096
+    assert abs(2.0 / math.sqrt(4096) - golden["corner_range_d4096"]) < 5e-4
+    assert 1.0 - math.sqrt(2.0 / 4096) > golden["corner_range_fraction"]
+
+
+def test_quantiser_rotation_and_heads_are_applied():
+    """y = x R_op per head, one scale over the whole row."""
+    w = I.small_workload(32, 20, heads=2, seed=20)
+    X = I.batch(w, 0)
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(32, 2, "bf16", R0)
+    sse, en, rows, codes = oc.quant_error(X, 4, True, True)
+    Rop = oc.R_op.astype(np.float64)
+    Y = np.concatenate([X[:, :16].astype(np.float64) @ Rop[0], X[:, 16:].astype(np.float64) @ Rop[1]], axis=1)
+    Yb = torch.from_numpy(Y).to(torch.bfloat16).to(torch.float64).numpy()
+    D = np.abs(Yb).max(axis=1, keepdims=True) / 7.0
+    q = np.clip(np.rint(Yb / D), -7, 7)
+    assert np.mean(q == codes) > 0.999
+    assert np.isclose(sse, ((Yb - D * q) ** 2).sum(), rtol=1e-4)
+    assert np.isclose(en, (Yb ** 2).sum(), rtol=1e-12)
+
+
+# --------------------------------------------------------------------------- whole stream (c1)
+
+def test_c1_stream_runs_and_improves():
+    w = I.WORKLOADS["c1"]
+    oc = O.OracleCalibrator(w.d, 1, "f32", I.initial_rotation(w), w.prox_lambda)
+    X0 = I.batch(w, 0)
+    before = oc.quant_error(X0)
+    objs = []
+    for b in range(w.n_batches):
+        oc.step_batch(I.batch(w, b))
+        objs.append(oc.objective()[0] / w.tokens_per_batch)
+        st = oc.update_rotation()[0]
+        assert st["orth_err"] < 1e-10 and np.isclose(st["inner"], st["nuclear"], rtol=1e-10)
+    after = oc.quant_error(X0)
+    assert objs[-1] < objs[0] and after[0] / after[1] < 0.6 * before[0] / before[1]
