@@ -1,0 +1,168 @@
+/*
+ * conqur.h -- C ABI of the MI355X (gfx950) hot path of ConQuR's online rotation
+ * calibration: rotate -> row-normalise -> hypercube-corner assign -> accumulate
+ * the cross-covariance -> closed-form orthogonal Procrustes (polar) update, plus
+ * the per-token symmetric fake-quantisation error of the rotated activations.
+ *
+ * Conventions (all matrices row-major, activations are rows, App. A "X_hat = X R"):
+ *   y_i  = x_i R                      the rotation maps row vectors; it is the
+ *                                     transpose of the R of Sec. 3 (which writes R x)
+ *   M    = sum_i (x_i/||x_i||)^T c_i  c_i = sgn(y_i)/sqrt(dh), sgn(0) = +1 (Eq. 2);
+ *                                     the transpose of Sec. 3.3's C = Z^T X~
+ *   R    <- polar(M) = U V^T          Sec. 3.3, for M = U S V^T
+ * With heads = h > 1 the row of width d is h independent blocks of width dh = d/h,
+ * each with its own rotation, statistics and update (App. A: the block-diagonal
+ * per-head rotation; Sec. 3.4 "a Procrustes problem per head").
+ *
+ * Pointers are tagged HOST or DEVICE below.  Every call returns a conqur_status;
+ * nothing throws across the boundary.  Calls enqueue their kernels on the stream
+ * given at init and return without waiting unless a HOST output is requested.
+ * A context is not thread safe.  The library never falls back to the CPU: every
+ * step below runs in HIP kernels, and a call fails with CONQUR_EHIP if the device
+ * or a launch fails.
+ */
+#ifndef CONQUR_H
+#define CONQUR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct conqur_ctx conqur_ctx; /* opaque; owns R, the rotate operand, M and all workspaces (device) */
+
+typedef enum {
+  CONQUR_OK = 0,
+  CONQUR_EINVAL = 1,    /* bad argument, shape, stride or alignment; nothing was enqueued        */
+  CONQUR_ESTATE = 2,    /* call not valid in this state (update with no accumulated row)         */
+  CONQUR_ENOMEM = 3,    /* device or host allocation failed                                      */
+  CONQUR_EHIP = 4,      /* a HIP call failed; conqur_last_error() holds the HIP error string      */
+  CONQUR_ENOCONV = 5,   /* polar iteration hit polar_max_iters; R holds the last iterate and the
+                           reported orthogonality error says how far it is from orthogonal        */
+  CONQUR_ENONFINITE = 6 /* (reported by update) rows with NaN/Inf were met and skipped           */
+} conqur_status;
+
+typedef enum { CONQUR_F32 = 0, CONQUR_BF16 = 1 } conqur_dtype;
+
+typedef struct {
+  uint32_t d;               /* row width of X; d % heads == 0, (d/heads) % 16 == 0, d/heads <= 8192 */
+  uint32_t heads;           /* 1 = one d x d rotation; h > 1 = h independent (d/h) x (d/h) problems */
+  uint32_t act_dtype;       /* conqur_dtype of X; the rotate operand is R rounded to this type      */
+  uint32_t max_tokens;      /* largest T passed to step_batch / quant_error (sizes the workspaces)  */
+  float prox_lambda;        /* 0: R <- polar(M), the paper's update (Sec. 3.3).  > 0: R <- polar(M +
+                               lambda * tau * R_prev), tau = ||M||_F / sqrt(dh): the proximal reading
+                               that makes the update unique when M is rank deficient               */
+  float polar_tol;          /* stop when ||X^T X - I||_F <= tol; 0 selects 5e-5                      */
+  uint32_t polar_max_iters; /* 0 selects 200                                                        */
+  int32_t device;           /* HIP device ordinal                                                   */
+  void* stream;             /* hipStream_t the caller owns (NULL = the device's default stream)      */
+} conqur_config;
+
+/* Per-head statistics of the rows accumulated since the last update (HOST struct). */
+typedef struct {
+  uint64_t rows;    /* rows that entered M                                                         */
+  uint64_t skipped; /* rows skipped: all-zero or non-finite head slice                             */
+  double l1;        /* L = sum_i ||y_i||_1 / ||x_i||_2 ; Eq. 1 equals 2*rows - 2*L/sqrt(dh)
+                       (the l1 identity of Sec. 3.2)                                               */
+} conqur_batch_stats;
+
+/* Per-head result of one Procrustes update (HOST struct). */
+typedef struct {
+  uint32_t iters;       /* polar iterations run (cheap + accurate)                                 */
+  uint32_t accurate;    /* how many of them ran in split (fp32-equivalent) arithmetic              */
+  double orth_err;      /* ||R^T R - I||_F of the stored fp32 R, as measured on the device          */
+  double inner;         /* <R_new, M>, the Procrustes objective value (nuclear norm at the optimum)  */
+  double m_fro;         /* ||M||_F                                                                  */
+  double ms;            /* device time of this update in milliseconds (all heads together)          */
+} conqur_update_stats;
+
+/*
+ * Create a context (Alg. 1 "initial rotation").  R0_host: HOST, heads*dh*dh floats,
+ * head-major, each block row-major and orthogonal (not checked).  Copied; the caller
+ * keeps ownership.  On success *out receives the context.  Allocates all device
+ * memory the other calls need; those calls allocate nothing.
+ */
+conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur_ctx** out);
+
+/*
+ * One batch of the statistics loop (Alg. 1 inner loop; Sec. 3.4): for every row
+ * x_i of X and every head, rotate with the operand copy of R, take the corner of
+ * the rotated row (Eq. 2), and add (x_i/||x_i||)^T c_i to M.  May be called many
+ * times before one update (Alg. 1 pools all sites of a mini-batch).
+ * X_dev: DEVICE, T rows of row_stride_elems elements of act_dtype, of which the
+ * first d are used; 16-byte aligned base and row pitch.  1 <= T <= max_tokens.
+ * The caller keeps ownership of X and may reuse it once the stream has passed
+ * this call's kernels.  Asynchronous; never touches the host.
+ */
+conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems);
+
+/*
+ * Read the per-head statistics accumulated since the last update.  stats_host:
+ * HOST array of `heads` entries.  Synchronises the stream.
+ */
+conqur_status conqur_get_batch_stats(conqur_ctx* ctx, conqur_batch_stats* stats_host);
+
+/*
+ * Orthogonal Procrustes update (Sec. 3.3): R <- polar(M + prox_lambda*tau*R) per
+ * head, computed on the device by a GEMM-only Newton-Schulz iteration; refreshes
+ * the rotate operand and clears M and the batch statistics (Alg. 1 starts every
+ * mini-batch with empty statistics).  stats_host: HOST array of `heads` entries or
+ * NULL.  Synchronises the stream (the iteration count is data dependent).
+ * Returns CONQUR_ESTATE if no row was accumulated, CONQUR_ENOCONV if the cap was
+ * hit (R is still replaced; stats->orth_err tells how good it is), and
+ * CONQUR_ENONFINITE (after a successful update) if rows were skipped as non-finite.
+ */
+conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* stats_host);
+
+/*
+ * Score the current rotation (App. B symmetric quantiser; Sec. 4.3 error metric):
+ * Y = X R_op per head, stored in act_dtype, then per token (one scale over the whole
+ * row of width d) D = max|y| / (2^(bits-1) - 1), q = D * round_half_even(y / D)
+ * clamped to the level range.  sse_host = sum (y - q)^2, energy_host = sum y^2
+ * (both HOST doubles).  X_dev as in conqur_step_batch.  bits in [2, 8].  Does not
+ * change the calibration state.  Synchronises the stream.
+ */
+conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems,
+                                 uint32_t bits, double* sse_host, double* energy_host);
+
+/*
+ * Copy state to the host / replace it (checkpointing, and teacher-forced parity
+ * tests).  R_host, M_host: HOST, heads*dh*dh floats or NULL.  n_rows_host: HOST,
+ * `heads` entries or NULL.  set_state(R) also refreshes the rotate operand;
+ * set_state(M) marks the statistics as holding rows (row count unknown -> 1).
+ * Both synchronise the stream.
+ */
+conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, uint64_t* n_rows_host);
+conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float* M_host);
+
+/*
+ * Debug / parity taps of the last conqur_step_batch: the corner signs as int8
+ * (+1 / -1; HOST, T*d, row-major like X) and the per-row norms (HOST, heads*T,
+ * head-major; 0 marks a skipped row).  Either may be NULL.  Synchronises.
+ */
+conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs_host, float* norms_host);
+
+/* Per-stage device times (ms) of the most recent call of each kind, measured with
+ * HIP events on the context's stream when timing is enabled (enable != 0 adds two
+ * event records per stage).  out_host: HOST, 8 floats:
+ * [0] step: prepare (norms + transposed operand)  [1] step: rotate+corner GEMM
+ * [2] step: accumulate GEMM                       [3] step: statistics reduction
+ * [4] update: whole polar update                  [5] quant: rotate GEMM
+ * [6] quant: error kernel                         [7] reserved                      */
+conqur_status conqur_set_timing(conqur_ctx* ctx, int enable);
+conqur_status conqur_get_timing(conqur_ctx* ctx, float* out_host);
+
+/* Last error text of this context (HOST string owned by the context; "" if none). */
+const char* conqur_last_error(const conqur_ctx* ctx);
+
+/* Release the context and all device memory it owns.  NULL is allowed. */
+void conqur_destroy(conqur_ctx* ctx);
+
+/* Library version string, e.g. "conqur-gfx950 0.1". */
+const char* conqur_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONQUR_H */

@@ -1,0 +1,201 @@
+"""Thin ctypes binding over libconqur.so (the C ABI declared in include/conqur.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory (tensors) and the stream handle.  There
+is no fallback: if the shared library is missing or the device call fails, the
+binding raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libconqur.so")
+
+OK, EINVAL, ESTATE, ENOMEM, EHIP, ENOCONV, ENONFINITE = range(7)
+STATUS_NAMES = ["OK", "EINVAL", "ESTATE", "ENOMEM", "EHIP", "ENOCONV", "ENONFINITE"]
+F32, BF16 = 0, 1
+
+EXPORTS = [
+    "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
+    "conqur_quant_error", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
+    "conqur_set_timing", "conqur_get_timing", "conqur_last_error", "conqur_destroy", "conqur_version",
+]
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_uint32), ("heads", ctypes.c_uint32), ("act_dtype", ctypes.c_uint32),
+                ("max_tokens", ctypes.c_uint32), ("prox_lambda", ctypes.c_float), ("polar_tol", ctypes.c_float),
+                ("polar_max_iters", ctypes.c_uint32), ("device", ctypes.c_int32), ("stream", ctypes.c_void_p)]
+
+
+class BatchStats(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_uint64), ("skipped", ctypes.c_uint64), ("l1", ctypes.c_double)]
+
+
+class UpdateStats(ctypes.Structure):
+    _fields_ = [("iters", ctypes.c_uint32), ("accurate", ctypes.c_uint32), ("orth_err", ctypes.c_double),
+                ("inner", ctypes.c_double), ("m_fro", ctypes.c_double), ("ms", ctypes.c_double)]
+
+
+class ConqurError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 7 else status}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libconqur.so; raises if it has not been built (run build.py / __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2605_10793_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u64, u32, i32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
+        L.conqur_init.restype = i32
+        L.conqur_init.argtypes = [ctypes.POINTER(Config), vp, ctypes.POINTER(vp)]
+        L.conqur_step_batch.restype = i32
+        L.conqur_step_batch.argtypes = [vp, vp, u64, u64]
+        L.conqur_get_batch_stats.restype = i32
+        L.conqur_get_batch_stats.argtypes = [vp, vp]
+        L.conqur_update_rotation.restype = i32
+        L.conqur_update_rotation.argtypes = [vp, vp]
+        L.conqur_quant_error.restype = i32
+        L.conqur_quant_error.argtypes = [vp, vp, u64, u64, u32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.conqur_get_state.restype = i32
+        L.conqur_get_state.argtypes = [vp, vp, vp, vp]
+        L.conqur_set_state.restype = i32
+        L.conqur_set_state.argtypes = [vp, vp, vp]
+        L.conqur_get_last_corners.restype = i32
+        L.conqur_get_last_corners.argtypes = [vp, vp, vp]
+        L.conqur_set_timing.restype = i32
+        L.conqur_set_timing.argtypes = [vp, i32]
+        L.conqur_get_timing.restype = i32
+        L.conqur_get_timing.argtypes = [vp, vp]
+        L.conqur_last_error.restype = ctypes.c_char_p
+        L.conqur_last_error.argtypes = [vp]
+        L.conqur_destroy.restype = None
+        L.conqur_destroy.argtypes = [vp]
+        L.conqur_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+class Calibrator:
+    """One context: `heads` rotations of width d/heads, their statistics and workspaces."""
+
+    def __init__(self, d: int, heads: int, dtype: str, R0: np.ndarray, max_tokens: int,
+                 prox_lambda: float = 0.0, polar_tol: float = 0.0, polar_max_iters: int = 0,
+                 device: int = 0, stream: Optional[int] = None):
+        import torch
+        self._lib = load()
+        self.d, self.heads, self.dh, self.dtype = d, heads, d // max(heads, 1), dtype
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+        cfg = Config(d, heads, BF16 if dtype == "bf16" else F32, max_tokens, prox_lambda, polar_tol,
+                     polar_max_iters, device, ctypes.c_void_p(stream))
+        R0 = np.ascontiguousarray(R0, dtype=np.float32)
+        if R0.size != heads * self.dh * self.dh:
+            raise ValueError("R0 must hold heads * dh * dh floats")
+        h = ctypes.c_void_p()
+        st = self._lib.conqur_init(ctypes.byref(cfg), _np_ptr(R0), ctypes.byref(h))
+        if st != OK:
+            raise ConqurError(st, "conqur_init failed")
+        self._h = h
+
+    def _check(self, st: int, allow: Tuple[int, ...] = ()) -> int:
+        if st != OK and st not in allow:
+            raise ConqurError(st, self._lib.conqur_last_error(self._h).decode())
+        return st
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.conqur_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _x(self, X) -> Tuple[int, int, int]:
+        import torch
+        want = torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        if X.dim() != 2 or X.stride(1) != 1 or not X.is_cuda or X.dtype != want or X.shape[1] < self.d:
+            raise ValueError(f"X must be a 2-D {want} device tensor with >= d columns and unit column stride")
+        return X.data_ptr(), X.shape[0], X.stride(0)
+
+    def step_batch(self, X) -> None:
+        p, T, stride = self._x(X)
+        self._check(self._lib.conqur_step_batch(self._h, p, T, stride))
+
+    def batch_stats(self) -> List[dict]:
+        arr = (BatchStats * self.heads)()
+        self._check(self._lib.conqur_get_batch_stats(self._h, arr))
+        return [dict(rows=int(a.rows), skipped=int(a.skipped), l1=float(a.l1)) for a in arr]
+
+    def objective(self) -> np.ndarray:
+        """Eq. 1 through the l1 identity (Sec. 3.2): 2*rows - 2*L/sqrt(dh), per head."""
+        s = self.batch_stats()
+        return np.array([2.0 * a["rows"] - 2.0 * a["l1"] / np.sqrt(float(self.dh)) for a in s])
+
+    def update_rotation(self, allow: Tuple[int, ...] = ()) -> Tuple[int, List[dict]]:
+        arr = (UpdateStats * self.heads)()
+        st = self._check(self._lib.conqur_update_rotation(self._h, arr), allow)
+        return st, [dict(iters=int(a.iters), accurate=int(a.accurate), orth_err=float(a.orth_err),
+                         inner=float(a.inner), m_fro=float(a.m_fro), ms=float(a.ms)) for a in arr]
+
+    def quant_error(self, X, bits: int = 4) -> Tuple[float, float]:
+        p, T, stride = self._x(X)
+        sse, en = ctypes.c_double(), ctypes.c_double()
+        self._check(self._lib.conqur_quant_error(self._h, p, T, stride, bits, ctypes.byref(sse), ctypes.byref(en)))
+        return sse.value, en.value
+
+    def get_state(self, want_R: bool = True, want_M: bool = True):
+        shape = (self.heads, self.dh, self.dh)
+        R = np.empty(shape, dtype=np.float32) if want_R else None
+        M = np.empty(shape, dtype=np.float32) if want_M else None
+        n = np.zeros(self.heads, dtype=np.uint64)
+        self._check(self._lib.conqur_get_state(self._h, _np_ptr(R), _np_ptr(M), _np_ptr(n)))
+        return R, M, n
+
+    def set_state(self, R: Optional[np.ndarray] = None, M: Optional[np.ndarray] = None) -> None:
+        R = None if R is None else np.ascontiguousarray(R, dtype=np.float32)
+        M = None if M is None else np.ascontiguousarray(M, dtype=np.float32)
+        self._check(self._lib.conqur_set_state(self._h, _np_ptr(R), _np_ptr(M)))
+
+    def last_corners(self, T: int):
+        S = np.empty((T, self.d), dtype=np.int8)
+        nrm = np.empty((self.heads, T), dtype=np.float32)
+        self._check(self._lib.conqur_get_last_corners(self._h, _np_ptr(S), _np_ptr(nrm)))
+        return S, nrm
+
+    def set_timing(self, enable: bool) -> None:
+        self._check(self._lib.conqur_set_timing(self._h, int(enable)))
+
+    def timing(self) -> dict:
+        out = np.zeros(8, dtype=np.float32)
+        self._check(self._lib.conqur_get_timing(self._h, _np_ptr(out)))
+        keys = ["prep", "rotate", "accumulate", "stats", "update", "quant_rotate", "quant_error"]
+        return {k: float(out[i]) for i, k in enumerate(keys)}
+
+
+def to_device(x: np.ndarray, dtype: str, device: str = "cuda:0"):
+    """float32 numpy [T, d] (bf16-representable for dtype 'bf16') -> device tensor of the activation dtype."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.to(device)

@@ -1,0 +1,508 @@
+// Host side of libconqur: context, argument checks, kernel sequencing and the
+// polar-iteration control loop.  All arithmetic of the method runs in the HIP
+// kernels of gemm_nt.hip / kernels.hip; there is no CPU fallback.
+#include "../../include/conqur.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "gemm_nt.h"
+#include "kernels.h"
+
+using namespace conqur;
+
+namespace {
+
+// K-segment schedules for products of bf16 split planes.  (a, b) multiplies plane a
+// of the left operand with plane b of the right one; smallest terms first.
+struct SegList { int n; int a[kMaxSegments]; int b[kMaxSegments]; };
+constexpr SegList kSeg1 = {1, {0}, {0}};
+constexpr SegList kSeg6 = {6, {2, 1, 0, 1, 0, 0}, {0, 1, 2, 0, 1, 0}};  // all terms down to 2^-24 relative
+constexpr SegList kSeg3x1 = {3, {2, 1, 0}, {0, 0, 0}};                   // 3-plane left operand, exact right operand
+
+enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_COUNT };
+
+}  // namespace
+
+struct conqur_ctx {
+  conqur_config cfg{};
+  int d = 0, heads = 0, dh = 0, np = 1;  // np: bf16 planes per activation operand (1 bf16, 3 fp32)
+  bool f32 = false;
+  int64_t tmax = 0, pitch = 0;            // pitch: token pitch of the transposed operands
+  hipStream_t stream = nullptr;
+  std::string err;
+
+  float* R = nullptr;          // [heads][dh][dh] fp32 master rotation
+  bf16_bits* RopT = nullptr;   // [np][heads][dh][dh] planes of R^T in the activation dtype (rotate operand)
+  float* M = nullptr;          // [heads][dh][dh]
+  bool m_empty = true;         // M holds no rows: the next accumulate overwrites it
+  bool have_rows = false;
+  bf16_bits* Xt = nullptr;     // [np][d][pitch] scaled, transposed activations (fp16 plane, or 3 bf16 planes for fp32 input)
+  bf16_bits* St = nullptr;     // [d][pitch] corner signs +-1, transposed (fp16, or bf16 for fp32 input)
+  bf16_bits* Xs = nullptr;     // fp32 activations only: [3][tmax][d] split planes of X
+  float *nrm = nullptr, *w = nullptr;  // [heads][tmax]
+  float* Lpart = nullptr;      // [heads][slabs][tmax]
+  int slabs_max = 0;
+  double* L = nullptr;         // [heads]
+  unsigned long long *rows = nullptr, *skipped = nullptr;
+  int* nonfinite = nullptr;
+  void* Y = nullptr;           // [tmax][d] rotated activations (quantiser score)
+  float *row_sse = nullptr, *row_en = nullptr;
+  double* qsum = nullptr;      // [2]
+  // polar workspaces
+  float *PX = nullptr, *PP = nullptr;              // iterate and polynomial factor, fp32
+  bf16_bits *PXn = nullptr, *PXt = nullptr, *PPn = nullptr;  // [3][heads][dh][dh] split planes
+  double *resid = nullptr, *fro2 = nullptr, *inner = nullptr;  // [heads]
+  int64_t last_T = 0;
+
+  bool timing = false;
+  hipEvent_t ev[ST_COUNT][2]{};
+  bool ev_valid[ST_COUNT]{};
+  std::vector<void*> allocs;
+};
+
+namespace {
+
+conqur_status fail(conqur_ctx* c, conqur_status st, const std::string& msg) {
+  if (c) c->err = msg;
+  return st;
+}
+conqur_status hip_fail(conqur_ctx* c, hipError_t e, const char* where) {
+  return fail(c, e == hipErrorOutOfMemory ? CONQUR_ENOMEM : CONQUR_EHIP, std::string(where) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(expr)                                        \
+  do {                                                       \
+    hipError_t e_ = (expr);                                  \
+    if (e_ != hipSuccess) return hip_fail(ctx, e_, #expr);   \
+  } while (0)
+
+template <typename T>
+hipError_t dev_alloc(conqur_ctx* c, T** p, size_t count) {
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, count * sizeof(T) + 256);
+  if (e != hipSuccess) return e;
+  c->allocs.push_back(q);
+  *p = reinterpret_cast<T*>(q);
+  return hipMemsetAsync(q, 0, count * sizeof(T) + 256, c->stream);
+}
+
+struct StageTimer {
+  conqur_ctx* c; int st;
+  StageTimer(conqur_ctx* c_, int st_) : c(c_), st(st_) {
+    if (c->timing) (void)hipEventRecord(c->ev[st][0], c->stream);
+  }
+  ~StageTimer() {
+    if (c->timing) { (void)hipEventRecord(c->ev[st][1], c->stream); c->ev_valid[st] = true; }
+  }
+};
+
+conqur_status check_x(conqur_ctx* ctx, const void* X, uint64_t T, uint64_t stride) {
+  if (!ctx) return CONQUR_EINVAL;
+  if (!X) return fail(ctx, CONQUR_EINVAL, "X_dev is NULL");
+  if (T < 1 || (int64_t)T > ctx->tmax) return fail(ctx, CONQUR_EINVAL, "T must be in [1, max_tokens]");
+  if (stride < (uint64_t)ctx->d) return fail(ctx, CONQUR_EINVAL, "row_stride_elems < d");
+  const uint64_t esz = ctx->f32 ? 4 : 2;
+  if ((reinterpret_cast<uintptr_t>(X) & 15) || ((stride * esz) & 15))
+    return fail(ctx, CONQUR_EINVAL, "X_dev base and row pitch must be 16-byte aligned");
+  return CONQUR_OK;
+}
+
+// Rotate GEMM: acc[i][j] = sum_k x_ik R_op[k][j] per head, as an NT product with
+// B = R_op^T.  fp32 activations go through 3 + 3 bf16 planes (6 segments).
+void rotate_args(conqur_ctx* c, const void* X, int64_t T, int64_t stride, GemmArgs* g) {
+  std::memset(g, 0, sizeof(*g));
+  const int64_t rplane = (int64_t)c->heads * c->dh * c->dh;
+  g->B = c->RopT; g->ldb = c->dh; g->batchB = (int64_t)c->dh * c->dh;
+  g->M = (int)T; g->N = c->dh; g->K = c->dh;
+  g->batchA = c->dh;
+  if (c->f32) {
+    g->A = c->Xs; g->lda = c->d;
+    g->nseg = kSeg6.n;
+    for (int s = 0; s < kSeg6.n; ++s) { g->a_seg[s] = kSeg6.a[s] * c->tmax * c->d; g->b_seg[s] = kSeg6.b[s] * rplane; }
+  } else {
+    g->A = reinterpret_cast<const bf16_bits*>(X); g->lda = stride;
+    g->nseg = 1;
+  }
+}
+
+conqur_status refresh_operand(conqur_ctx* ctx) {
+  const int64_t plane = (int64_t)ctx->heads * ctx->dh * ctx->dh;
+  HIP_TRY(launch_pack(ctx->R, ctx->heads, ctx->dh, ctx->dh, ctx->np, nullptr, ctx->RopT, plane, ctx->stream));
+  return CONQUR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* conqur_version(void) { return "conqur-gfx950 0.1"; }
+
+const char* conqur_last_error(const conqur_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+void conqur_destroy(conqur_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->cfg.device);
+  (void)hipStreamSynchronize(ctx->stream);
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  for (int s = 0; s < ST_COUNT; ++s)
+    for (int k = 0; k < 2; ++k)
+      if (ctx->ev[s][k]) (void)hipEventDestroy(ctx->ev[s][k]);
+  delete ctx;
+}
+
+conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur_ctx** out) {
+  if (!cfg || !R0_host || !out) return CONQUR_EINVAL;
+  *out = nullptr;
+  if (cfg->d == 0 || cfg->heads == 0 || cfg->d % cfg->heads) return CONQUR_EINVAL;
+  const uint32_t dh = cfg->d / cfg->heads;
+  if (dh % 16 || dh > 8192 || cfg->d > 65536) return CONQUR_EINVAL;
+  if (cfg->act_dtype != CONQUR_F32 && cfg->act_dtype != CONQUR_BF16) return CONQUR_EINVAL;
+  if (cfg->max_tokens == 0 || cfg->max_tokens > (1u << 22)) return CONQUR_EINVAL;
+  if (!(cfg->prox_lambda >= 0.0f) || !(cfg->polar_tol >= 0.0f)) return CONQUR_EINVAL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return CONQUR_EHIP;
+  if (hipSetDevice(cfg->device) != hipSuccess) return CONQUR_EHIP;
+
+  conqur_ctx* ctx = new (std::nothrow) conqur_ctx();
+  if (!ctx) return CONQUR_ENOMEM;
+  ctx->cfg = *cfg;
+  if (ctx->cfg.polar_tol == 0.0f) ctx->cfg.polar_tol = 5e-5f;
+  if (ctx->cfg.polar_max_iters == 0) ctx->cfg.polar_max_iters = 200;
+  ctx->d = (int)cfg->d; ctx->heads = (int)cfg->heads; ctx->dh = (int)dh;
+  ctx->f32 = cfg->act_dtype == CONQUR_F32;
+  ctx->np = ctx->f32 ? 3 : 1;
+  ctx->tmax = cfg->max_tokens;
+  ctx->pitch = round_up(ctx->tmax, 64);
+  ctx->stream = reinterpret_cast<hipStream_t>(cfg->stream);
+
+  const size_t blk = (size_t)ctx->heads * dh * dh;
+  const size_t d = ctx->d, tmax = ctx->tmax, pitch = ctx->pitch, np = ctx->np;
+  // the widest tile the rotate GEMM can pick is 64 columns per slab pair -> slabs <= 2*ceil(dh/64)
+  ctx->slabs_max = 2 * (int)((dh + 63) / 64);
+  hipError_t e = hipSuccess;
+  auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  A(dev_alloc(ctx, &ctx->R, blk));
+  A(dev_alloc(ctx, &ctx->RopT, np * blk));
+  A(dev_alloc(ctx, &ctx->M, blk));
+  A(dev_alloc(ctx, &ctx->Xt, np * d * pitch));
+  A(dev_alloc(ctx, &ctx->St, d * pitch));
+  if (ctx->f32) A(dev_alloc(ctx, &ctx->Xs, 3 * tmax * d));
+  A(dev_alloc(ctx, &ctx->nrm, (size_t)ctx->heads * tmax));
+  A(dev_alloc(ctx, &ctx->w, (size_t)ctx->heads * tmax));
+  A(dev_alloc(ctx, &ctx->Lpart, (size_t)ctx->heads * ctx->slabs_max * tmax));
+  A(dev_alloc(ctx, &ctx->L, (size_t)ctx->heads));
+  A(dev_alloc(ctx, &ctx->rows, (size_t)ctx->heads));
+  A(dev_alloc(ctx, &ctx->skipped, (size_t)ctx->heads));
+  A(dev_alloc(ctx, &ctx->nonfinite, (size_t)4));
+  A(dev_alloc(ctx, reinterpret_cast<char**>(&ctx->Y), tmax * d * (ctx->f32 ? 4 : 2)));
+  A(dev_alloc(ctx, &ctx->row_sse, tmax));
+  A(dev_alloc(ctx, &ctx->row_en, tmax));
+  A(dev_alloc(ctx, &ctx->qsum, (size_t)2));
+  A(dev_alloc(ctx, &ctx->PX, blk));
+  A(dev_alloc(ctx, &ctx->PP, blk));
+  A(dev_alloc(ctx, &ctx->PXn, 3 * blk));
+  A(dev_alloc(ctx, &ctx->PXt, 3 * blk));
+  A(dev_alloc(ctx, &ctx->PPn, 3 * blk));
+  A(dev_alloc(ctx, &ctx->resid, (size_t)ctx->heads));
+  A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
+  A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
+  for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
+    for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreate(&ctx->ev[s][k]);
+  if (e == hipSuccess) e = hipMemcpyAsync(ctx->R, R0_host, blk * sizeof(float), hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess) e = launch_pack(ctx->R, ctx->heads, ctx->dh, ctx->dh, ctx->np, nullptr, ctx->RopT, (int64_t)blk, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) {
+    const conqur_status st = e == hipErrorOutOfMemory ? CONQUR_ENOMEM : CONQUR_EHIP;
+    conqur_destroy(ctx);
+    return st;
+  }
+  *out = ctx;
+  return CONQUR_OK;
+}
+
+conqur_status conqur_set_timing(conqur_ctx* ctx, int enable) {
+  if (!ctx) return CONQUR_EINVAL;
+  ctx->timing = enable != 0;
+  return CONQUR_OK;
+}
+
+conqur_status conqur_get_timing(conqur_ctx* ctx, float* out) {
+  if (!ctx || !out) return CONQUR_EINVAL;
+  HIP_TRY(hipStreamSynchronize(ctx->stream));
+  for (int s = 0; s < 8; ++s) out[s] = 0.0f;
+  for (int s = 0; s < ST_COUNT; ++s)
+    if (ctx->ev_valid[s]) HIP_TRY(hipEventElapsedTime(&out[s], ctx->ev[s][0], ctx->ev[s][1]));
+  return CONQUR_OK;
+}
+
+conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+  const int64_t Tk = round_up(T, 64);
+  hipStream_t s = ctx->stream;
+  {
+    StageTimer tm(ctx, ST_PREP);
+    HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, s));
+    HIP_TRY(launch_transpose_scale(X, ctx->f32, T, Tk, stride, ctx->d, ctx->dh, ctx->w, ctx->tmax, ctx->Xt, ctx->pitch,
+                                   (int64_t)ctx->d * ctx->pitch, ctx->np, s));
+    if (ctx->f32)
+      HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
+  }
+  int slabs = 0;
+  {
+    StageTimer tm(ctx, ST_ROTATE);
+    GemmArgs g;
+    rotate_args(ctx, X, T, stride, &g);
+    g.C = ctx->St; g.ldc = ctx->pitch; g.batchC = (int64_t)ctx->dh * ctx->pitch;
+    g.st_rows_valid = ctx->pitch;
+    g.sign_f16 = ctx->f32 ? 0 : 1;   // the accumulate GEMM runs in fp16 for bf16 activations
+    slabs = gemm_sign_slabs(g.M, g.N, ctx->heads);
+    if (slabs > ctx->slabs_max) return fail(ctx, CONQUR_EHIP, "internal: slab count exceeds workspace");
+    g.Lpart = ctx->Lpart; g.ldl = ctx->tmax;
+    HIP_TRY(launch_gemm_nt(g, EPI_SIGN, ctx->heads, s));
+  }
+  {
+    StageTimer tm(ctx, ST_ACCUM);
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ctx->Xt; g.lda = ctx->pitch; g.batchA = (int64_t)ctx->dh * ctx->pitch;
+    g.B = ctx->St; g.ldb = ctx->pitch; g.batchB = (int64_t)ctx->dh * ctx->pitch;
+    g.M = ctx->dh; g.N = ctx->dh; g.K = (int)Tk;
+    const SegList& sl = ctx->f32 ? kSeg3x1 : kSeg1;
+    g.nseg = sl.n;
+    for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * (int64_t)ctx->d * ctx->pitch; g.b_seg[q] = 0; }
+    g.C = ctx->M; g.ldc = ctx->dh; g.batchC = (int64_t)ctx->dh * ctx->dh;
+    g.accumulate = ctx->m_empty ? 0 : 1;
+    g.ab_f16 = ctx->f32 ? 0 : 1;
+    HIP_TRY(launch_gemm_nt(g, EPI_F32, ctx->heads, s));
+  }
+  {
+    StageTimer tm(ctx, ST_STATS);
+    HIP_TRY(launch_reduce_stats(ctx->Lpart, slabs, ctx->tmax, ctx->nrm, ctx->tmax, T, ctx->heads, ctx->L, ctx->rows,
+                                ctx->skipped, s));
+  }
+  ctx->m_empty = false;
+  ctx->have_rows = true;
+  ctx->last_T = T;
+  return CONQUR_OK;
+}
+
+conqur_status conqur_get_batch_stats(conqur_ctx* ctx, conqur_batch_stats* out) {
+  if (!ctx || !out) return CONQUR_EINVAL;
+  const int h = ctx->heads;
+  std::vector<double> L(h);
+  std::vector<unsigned long long> rows(h), skipped(h);
+  HIP_TRY(hipMemcpyAsync(L.data(), ctx->L, h * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+  HIP_TRY(hipMemcpyAsync(rows.data(), ctx->rows, h * sizeof(unsigned long long), hipMemcpyDeviceToHost, ctx->stream));
+  HIP_TRY(hipMemcpyAsync(skipped.data(), ctx->skipped, h * sizeof(unsigned long long), hipMemcpyDeviceToHost, ctx->stream));
+  HIP_TRY(hipStreamSynchronize(ctx->stream));
+  for (int i = 0; i < h; ++i) { out[i].rows = rows[i]; out[i].skipped = skipped[i]; out[i].l1 = L[i]; }
+  return CONQUR_OK;
+}
+
+conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) {
+  if (!ctx) return CONQUR_EINVAL;
+  if (!ctx->have_rows) return fail(ctx, CONQUR_ESTATE, "update_rotation: no rows accumulated since the last update");
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  hipStream_t s = ctx->stream;
+  const int h = ctx->heads, dh = ctx->dh;
+  const int64_t blk = (int64_t)dh * dh, plane = (int64_t)h * blk;
+  const bool timed = ctx->timing || out;
+  if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][0], s));
+
+  HIP_TRY(launch_fill_zero(ctx->fro2, h * sizeof(double), s));
+  HIP_TRY(launch_fill_zero(ctx->inner, h * sizeof(double), s));
+  HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->fro2, s));
+  HIP_TRY(launch_polar_start(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, ctx->PX, s));
+
+  auto seg_fill = [&](GemmArgs& g, const SegList& sl) {
+    g.nseg = sl.n;
+    for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
+  };
+  std::vector<double> resid(h);
+  // Newton-Schulz: X <- X (1.5 I - 0.5 X^T X).  Cheap iterations use single bf16
+  // planes; once the residual is at the bf16 floor the iteration switches to
+  // 3-plane splits (fp32-equivalent products) until ||X^T X - I||_F <= tol.
+  const double tol = ctx->cfg.polar_tol;
+  const double switch_at = std::sqrt((double)dh) / 128.0;
+  bool accurate = false, converged = false;
+  const bool trace = std::getenv("CONQUR_TRACE") != nullptr;
+  uint32_t iters = 0, acc_iters = 0;
+  double res_max = 0.0, prev_res = 1e300, best_res = 1e300;
+  int since_best = 0, kicks = 0;
+  for (uint32_t it = 0; it <= ctx->cfg.polar_max_iters; ++it) {
+    const int np = accurate ? 3 : 1;
+    const SegList& sl = accurate ? kSeg6 : kSeg1;
+    HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np, ctx->PXn, ctx->PXt, plane, s));
+    HIP_TRY(launch_fill_zero(ctx->resid, h * sizeof(double), s));
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ctx->PXt; g.B = ctx->PXt; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.M = g.N = g.K = dh;
+    seg_fill(g, sl);
+    g.C = ctx->PP; g.ldc = dh; g.batchC = blk; g.resid = ctx->resid; g.coef_i = 1.5f; g.coef_g = -0.5f;
+    HIP_TRY(launch_gemm_nt(g, EPI_GRAM, h, s));
+    HIP_TRY(hipMemcpyAsync(resid.data(), ctx->resid, h * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    res_max = 0.0;
+    for (int q = 0; q < h; ++q) res_max = std::max(res_max, std::sqrt(resid[q]));
+    if (!std::isfinite(res_max)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
+    if (trace) std::fprintf(stderr, "[conqur] polar it=%u mode=%s resid_F=%.6e\n", it, accurate ? "split3" : "bf16", res_max);
+    if (accurate && res_max <= tol) { converged = true; break; }
+    if (!accurate && (res_max <= switch_at || (res_max < 0.45 && res_max > 0.7 * prev_res))) {
+      accurate = true;   // redo this Gram in split arithmetic before applying it
+      prev_res = 1e300;
+      continue;
+    }
+    if (it == ctx->cfg.polar_max_iters) break;
+    prev_res = res_max;
+    // A singular value that is exactly zero together with an exact symmetry of M (e.g.
+    // two identical columns, which identical corner-sign columns produce) is preserved
+    // by the iteration, rounding included.  After a long plateau, nudge the iterate
+    // towards the previous rotation: on the stuck directions every completion is
+    // optimal, and this one is the nearest to R_prev.
+    if (res_max < 0.999 * best_res) { best_res = res_max; since_best = 0; }
+    else if (res_max > 0.45 && ++since_best >= 40 && kicks < 3) {
+      HIP_TRY(launch_axpy(ctx->PX, ctx->R, plane, 1.0f / 256.0f, s));
+      ++kicks; since_best = 0; best_res = 1e300;
+      continue;
+    }
+    HIP_TRY(launch_pack(ctx->PP, h, dh, dh, np, ctx->PPn, nullptr, plane, s));
+    std::memset(&g, 0, sizeof(g));
+    g.A = ctx->PXn; g.B = ctx->PPn; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.M = g.N = g.K = dh;
+    seg_fill(g, sl);
+    g.C = ctx->PX; g.ldc = dh; g.batchC = blk; g.accumulate = 0;
+    HIP_TRY(launch_gemm_nt(g, EPI_F32, h, s));
+    ++iters;
+    if (accurate) ++acc_iters;
+  }
+  HIP_TRY(launch_polar_finish(ctx->PX, ctx->M, h, blk, ctx->R, ctx->inner, s));
+  conqur_status st = refresh_operand(ctx);
+  if (st != CONQUR_OK) return st;
+  // statistics restart empty (Alg. 1): M is overwritten by the next accumulate
+  HIP_TRY(launch_fill_zero(ctx->L, h * sizeof(double), s));
+  HIP_TRY(launch_fill_zero(ctx->rows, h * sizeof(unsigned long long), s));
+  HIP_TRY(launch_fill_zero(ctx->skipped, h * sizeof(unsigned long long), s));
+  if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
+  ctx->ev_valid[ST_UPDATE] = timed;
+  int nonfinite = 0;
+  std::vector<double> inner(h), fro2(h);
+  HIP_TRY(hipMemcpyAsync(inner.data(), ctx->inner, h * sizeof(double), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(fro2.data(), ctx->fro2, h * sizeof(double), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(&nonfinite, ctx->nonfinite, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(launch_fill_zero(ctx->nonfinite, sizeof(int), s));
+  HIP_TRY(hipStreamSynchronize(s));
+  ctx->m_empty = true;
+  ctx->have_rows = false;
+  if (out) {
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, ctx->ev[ST_UPDATE][0], ctx->ev[ST_UPDATE][1]));
+    for (int q = 0; q < h; ++q) {
+      out[q].iters = iters; out[q].accurate = acc_iters;
+      out[q].orth_err = std::sqrt(resid[q]);
+      out[q].inner = inner[q]; out[q].m_fro = std::sqrt(fro2[q]); out[q].ms = ms;
+    }
+  }
+  if (!converged) return fail(ctx, CONQUR_ENOCONV, "update_rotation: polar iteration hit polar_max_iters");
+  if (nonfinite) return fail(ctx, CONQUR_ENONFINITE, "rows with non-finite values were skipped");
+  return CONQUR_OK;
+}
+
+conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, uint32_t bits,
+                                 double* sse, double* energy) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  if (bits < 2 || bits > 8) return fail(ctx, CONQUR_EINVAL, "bits must be in [2, 8]");
+  if (!sse || !energy) return fail(ctx, CONQUR_EINVAL, "sse_host / energy_host is NULL");
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+  hipStream_t s = ctx->stream;
+  {
+    StageTimer tm(ctx, ST_QROT);
+    if (ctx->f32)
+      HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
+    GemmArgs g;
+    rotate_args(ctx, X, T, stride, &g);
+    g.C = ctx->Y; g.ldc = ctx->d; g.batchC = ctx->dh; g.c_is_f32 = ctx->f32;
+    HIP_TRY(launch_gemm_nt(g, EPI_ACT, ctx->heads, s));
+  }
+  {
+    StageTimer tm(ctx, ST_QERR);
+    HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, ctx->row_sse, ctx->row_en, ctx->qsum, s));
+  }
+  double host[2] = {0.0, 0.0};
+  HIP_TRY(hipMemcpyAsync(host, ctx->qsum, sizeof(host), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  *sse = host[0];
+  *energy = host[1];
+  return CONQUR_OK;
+}
+
+conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, uint64_t* n_rows) {
+  if (!ctx) return CONQUR_EINVAL;
+  const size_t blk = (size_t)ctx->heads * ctx->dh * ctx->dh;
+  hipStream_t s = ctx->stream;
+  if (R_host) HIP_TRY(hipMemcpyAsync(R_host, ctx->R, blk * sizeof(float), hipMemcpyDeviceToHost, s));
+  if (M_host) {
+    if (ctx->m_empty) std::memset(M_host, 0, blk * sizeof(float));
+    else HIP_TRY(hipMemcpyAsync(M_host, ctx->M, blk * sizeof(float), hipMemcpyDeviceToHost, s));
+  }
+  std::vector<unsigned long long> rows(ctx->heads);
+  if (n_rows) HIP_TRY(hipMemcpyAsync(rows.data(), ctx->rows, ctx->heads * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (n_rows) for (int i = 0; i < ctx->heads; ++i) n_rows[i] = rows[i];
+  return CONQUR_OK;
+}
+
+conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float* M_host) {
+  if (!ctx) return CONQUR_EINVAL;
+  const size_t blk = (size_t)ctx->heads * ctx->dh * ctx->dh;
+  hipStream_t s = ctx->stream;
+  if (R_host) {
+    HIP_TRY(hipMemcpyAsync(ctx->R, R_host, blk * sizeof(float), hipMemcpyHostToDevice, s));
+    conqur_status st = refresh_operand(ctx);
+    if (st != CONQUR_OK) return st;
+  }
+  if (M_host) {
+    HIP_TRY(hipMemcpyAsync(ctx->M, M_host, blk * sizeof(float), hipMemcpyHostToDevice, s));
+    ctx->m_empty = false;
+    ctx->have_rows = true;
+  }
+  HIP_TRY(hipStreamSynchronize(s));
+  return CONQUR_OK;
+}
+
+conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs, float* norms) {
+  if (!ctx) return CONQUR_EINVAL;
+  if (ctx->last_T == 0) return fail(ctx, CONQUR_ESTATE, "no step_batch yet");
+  const int64_t T = ctx->last_T, d = ctx->d, pitch = ctx->pitch;
+  hipStream_t s = ctx->stream;
+  std::vector<float> nrm((size_t)ctx->heads * T);
+  HIP_TRY(hipMemcpy2DAsync(nrm.data(), T * sizeof(float), ctx->nrm, ctx->tmax * sizeof(float), T * sizeof(float), ctx->heads,
+                           hipMemcpyDeviceToHost, s));
+  std::vector<bf16_bits> st;
+  if (signs) {
+    st.resize((size_t)d * T);
+    HIP_TRY(hipMemcpy2DAsync(st.data(), T * sizeof(bf16_bits), ctx->St, pitch * sizeof(bf16_bits), T * sizeof(bf16_bits), d,
+                             hipMemcpyDeviceToHost, s));
+  }
+  HIP_TRY(hipStreamSynchronize(s));
+  if (norms) std::memcpy(norms, nrm.data(), nrm.size() * sizeof(float));
+  if (signs)
+    for (int64_t j = 0; j < d; ++j) {
+      const float* nh = nrm.data() + (j / ctx->dh) * T;
+      for (int64_t i = 0; i < T; ++i)
+        signs[i * d + j] = nh[i] > 0.0f ? ((st[j * T + i] & 0x8000) ? -1 : 1) : 0;
+    }
+  return CONQUR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// bf16 MFMA GEMM for gfx950, "NT" form: both operands are K-contiguous,
+//   acc[m][n] = sum_seg sum_k A[seg.a + m*lda + k] * B[seg.b + n*ldb + k]    (fp32 accumulate)
+// followed by one of a few fused epilogues.  Every dense contraction of the
+// calibration path (rotate, accumulate, Gram, polynomial apply) is this kernel:
+// operands that are K-strided in their natural layout are produced transposed by
+// the kernel that writes them, and fp32-accurate products are obtained by feeding
+// bf16 split planes as several K-segments (hi*hi, hi*mid, mid*hi, ...).
+#pragma once
+#include "common.h"
+
+namespace conqur {
+
+enum GemmEpilogue : int {
+  EPI_SIGN = 0,  // corner signs, transposed: St[n][m] = +-1 (bf16), and per-row sum_n |acc| partials
+  EPI_ACT = 1,   // Y[m][n] = acc, stored as bf16 or fp32 (rotated activations for the quantiser score)
+  EPI_F32 = 2,   // C[m][n] = acc (+ C[m][n] if accumulate), fp32
+  EPI_GRAM = 3,  // P[m][n] = coef_i*[m==n] + coef_g*acc (fp32) and resid += sum (acc - [m==n])^2
+};
+
+constexpr int kMaxSegments = 6;
+
+struct GemmArgs {
+  const bf16_bits* A;
+  const bf16_bits* B;
+  int64_t lda, ldb;        // row pitch in elements (multiples of 8)
+  int64_t batchA, batchB;  // element offset between batch entries (grid.z)
+  int M, N, K;             // K per segment, a multiple of 8
+  int ab_f16;              // operands hold fp16 instead of bf16 (EPI_F32 only)
+  int nseg;
+  int64_t a_seg[kMaxSegments];  // element offsets of each K-segment
+  int64_t b_seg[kMaxSegments];
+  // epilogue
+  void* C;                 // EPI_SIGN: bf16 St; EPI_ACT: bf16/f32 Y; EPI_F32 / EPI_GRAM: fp32
+  int64_t ldc, batchC;
+  int c_is_f32;            // EPI_ACT: element type of C
+  int accumulate;          // EPI_F32: add to C instead of overwriting
+  int64_t st_rows_valid;   // EPI_SIGN: St rows hold this many m entries (padded pitch), multiple of 4
+  int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
+  float* Lpart;            // EPI_SIGN: [batch][slabs][ldl] partial sums of |acc| over the slab's columns
+  int64_t ldl;             //           slabs = 2 * tiles_n
+  double* resid;           // EPI_GRAM: [batch] sum of squares of (acc - I)
+  float coef_i, coef_g;    // EPI_GRAM
+};
+
+// Enqueue the GEMM on `stream`.  Returns hipSuccess or the launch error.
+hipError_t launch_gemm_nt(const GemmArgs& args, GemmEpilogue epi, int batch, hipStream_t stream);
+
+// Number of column slabs the EPI_SIGN epilogue writes for an N-wide problem
+// (depends on the tile the launcher picks for (M, N, batch)).
+int gemm_sign_slabs(int M, int N, int batch);
+
+}  // namespace conqur

@@ -1,0 +1,57 @@
+// Non-GEMM kernels of the calibration path: row norms, scaled/transposed operand
+// preparation, bf16 split packing, statistics reductions, polar start/finish and
+// the bandwidth-bound fake-quantisation error kernel.  Launch wrappers only; each
+// returns the launch status.
+#pragma once
+#include "common.h"
+
+namespace conqur {
+
+// n_i = ||x_i||_2 over each head slice; w_i = 1/(n_i*sqrt(dh)), or 0 for a row that is
+// all zero or holds a non-finite value (then nrm = 0 and *nonfinite is raised for NaN/Inf).
+hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh,
+                            float* nrm, float* w, int64_t ldn, int* nonfinite, hipStream_t s);
+
+// Xt[p][k][i] = x_ik * w_{head(k), i} for i < T, 0 for T <= i < Tk.  np = 1 (bf16 activations):
+// one fp16 plane; np = 3 (fp32 activations): three bf16 split planes (exact).
+hipError_t launch_transpose_scale(const void* X, int x_is_f32, int64_t T, int64_t Tk, int64_t stride, int d, int dh,
+                                  const float* w, int64_t ldn, bf16_bits* Xt, int64_t pitch, int64_t plane, int np,
+                                  hipStream_t s);
+
+// Xs[p][i][k] = split_p(x_ik), fp32 activations only (3 planes).
+hipError_t launch_split_rows(const float* X, int64_t T, int64_t stride, int d, bf16_bits* Xs, int64_t plane,
+                             hipStream_t s);
+
+// Split an fp32 matrix batch [batch][rows][cols] into np bf16 planes, in natural
+// layout (outN[p][b][r][c]) and/or transposed (outT[p][b][c][r]); either may be null.
+hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
+                       int64_t plane, hipStream_t s);
+
+// L[h] += sum_i (sum_slab Lpart[h][slab][i]) / nrm[h][i]; rows/skipped counts.
+hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
+                               int heads, double* L, unsigned long long* rows, unsigned long long* skipped,
+                               hipStream_t s);
+
+// fro2[h] = sum M_h^2 (fro2 must be zero on entry).
+hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s);
+
+// X0 = (M + lambda*tau*R) / alpha with tau = ||M||_F/sqrt(dh), alpha = ||M||_F (1 + lambda);
+// a head with M = 0 starts from R itself.
+hipError_t launch_polar_start(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2,
+                              float* X, hipStream_t s);
+
+// X += kappa * R over n elements (all heads).
+hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s);
+
+// R = X and inner[h] = <X_h, M_h> (inner must be zero on entry).
+hipError_t launch_polar_finish(const float* X, const float* M, int heads, int64_t n, float* R, double* inner,
+                               hipStream_t s);
+
+// Per-row symmetric fake-quantisation error of Y [T][ld] (bf16 or fp32), then the
+// sums over rows: out[0] = SSE, out[1] = energy.
+hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,
+                              float* row_en, double* out, hipStream_t s);
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+}  // namespace conqur

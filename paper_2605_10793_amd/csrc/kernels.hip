@@ -1,0 +1,490 @@
+// Non-GEMM kernels of the calibration path (see kernels.h).
+#include "kernels.h"
+
+namespace conqur {
+
+namespace {
+
+__device__ __forceinline__ void unpack8(const uint4& v, float* f) {
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+// bf16 split of an fp32 value: x ~= p0 + p1 + p2 (exact for 24-bit significands).
+template <int NP>
+__device__ __forceinline__ void split_bf16(float x, bf16_bits* p) {
+  float r = x;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    p[i] = f32_to_bf16(r);
+    r -= bf16_to_f32(p[i]);
+  }
+}
+
+__device__ __forceinline__ double block_sum_d(double v, double* sh) {
+  v = wave_sum_d(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sh[i];
+  return t;
+}
+
+// ---------------------------------------------------------------- row norms
+template <bool F32>
+__global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, int64_t T, int64_t stride, int heads, int dh,
+                                                   float* __restrict__ nrm, float* __restrict__ w, int64_t ldn,
+                                                   int* __restrict__ nonfinite) {
+  const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (gw >= T * heads) return;
+  const int64_t i = gw / heads;
+  const int h = (int)(gw - i * heads);
+  float ss = 0.0f;
+  if constexpr (F32) {
+    const float* x = reinterpret_cast<const float*>(X) + i * stride + (int64_t)h * dh;
+    for (int c = lane; c < dh / 4; c += 64) {
+      const float4 v = *reinterpret_cast<const float4*>(x + c * 4);
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  } else {
+    const bf16_bits* x = reinterpret_cast<const bf16_bits*>(X) + i * stride + (int64_t)h * dh;
+    for (int c = lane; c < dh / 8; c += 64) {
+      float f[8];
+      unpack8(*reinterpret_cast<const uint4*>(x + c * 8), f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
+  }
+  ss = wave_sum(ss);
+  if (lane == 0) {
+    float n = 0.0f, wi = 0.0f;
+    if (!isfinite(ss)) {
+      atomicOr(nonfinite, 1);
+    } else if (ss > 0.0f) {
+      n = sqrtf(ss);
+      wi = 1.0f / (n * sqrtf((float)dh));
+    }
+    nrm[(int64_t)h * ldn + i] = n;
+    w[(int64_t)h * ldn + i] = wi;
+  }
+}
+
+// ---------------------------------------------------------------- scaled transpose
+template <bool F32, int NP>
+__global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict__ X, int64_t T, int64_t stride, int d, int dh,
+                                                         const float* __restrict__ w, int64_t ldn,
+                                                         bf16_bits* __restrict__ Xt, int64_t pitch, int64_t plane) {
+  __shared__ float tile[64][65];
+  const int64_t i0 = (int64_t)blockIdx.x * 64;
+  const int k0 = blockIdx.y * 64;
+  const int t = threadIdx.x;
+  {
+    const int c = t & 7;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int r = (t >> 3) + pass * 32;
+      const int64_t i = i0 + r;
+      const int k = k0 + c * 8;
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = 0.0f;
+      if (i < T && k < d) {
+        const float wi = w[(int64_t)(k / dh) * ldn + i];
+        if constexpr (F32) {
+          const float* x = reinterpret_cast<const float*>(X) + i * stride + k;
+          const float4 a = *reinterpret_cast<const float4*>(x), b = *reinterpret_cast<const float4*>(x + 4);
+          f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+        } else {
+          unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_bits*>(X) + i * stride + k), f);
+        }
+        // a skipped row has w = 0; its values may be Inf/NaN, so select instead of multiplying
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (wi != 0.0f) ? f[e] * wi : 0.0f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tile[r][c * 8 + e] = f[e];
+    }
+  }
+  __syncthreads();
+  {
+    const int tc = t & 7;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int kl = (t >> 3) + pass * 32;
+      const int k = k0 + kl;
+      if (k >= d) continue;
+      bf16_bits out[NP][8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if constexpr (NP == 1) {
+          out[0][e] = f32_to_f16(tile[tc * 8 + e][kl]);  // |x^| <= 1: fp16 keeps 11 significant bits
+        } else {
+          bf16_bits p[NP];
+          split_bf16<NP>(tile[tc * 8 + e][kl], p);
+#pragma unroll
+          for (int q = 0; q < NP; ++q) out[q][e] = p[q];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < NP; ++q) {
+        uint4 v;
+        v.x = out[q][0] | ((uint32_t)out[q][1] << 16); v.y = out[q][2] | ((uint32_t)out[q][3] << 16);
+        v.z = out[q][4] | ((uint32_t)out[q][5] << 16); v.w = out[q][6] | ((uint32_t)out[q][7] << 16);
+        *reinterpret_cast<uint4*>(Xt + q * plane + (int64_t)k * pitch + i0 + tc * 8) = v;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- fp32 rows -> 3 bf16 planes
+__global__ void __launch_bounds__(256) k_split_rows(const float* __restrict__ X, int64_t T, int64_t stride, int d,
+                                                    bf16_bits* __restrict__ Xs, int64_t plane) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one per 4 elements
+  const int per_row = d / 4;
+  if (idx >= T * per_row) return;
+  const int64_t i = idx / per_row;
+  const int k = (int)(idx - i * per_row) * 4;
+  const float4 v = *reinterpret_cast<const float4*>(X + i * stride + k);
+  const float f[4] = {v.x, v.y, v.z, v.w};
+  bf16_bits p[4][3];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) split_bf16<3>(f[e], p[e]);
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    uint2 o;
+    o.x = p[0][q] | ((uint32_t)p[1][q] << 16);
+    o.y = p[2][q] | ((uint32_t)p[3][q] << 16);
+    *reinterpret_cast<uint2*>(Xs + q * plane + i * d + k) = o;
+  }
+}
+
+// ---------------------------------------------------------------- fp32 matrix -> bf16 planes (natural / transposed)
+template <int NP>
+__global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int rows, int cols, bf16_bits* __restrict__ outN,
+                                              bf16_bits* __restrict__ outT, int64_t plane) {
+  __shared__ float tile[64][65];
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int64_t boff = (int64_t)blockIdx.z * rows * cols;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int r = (t >> 4) + pass * 16;
+    const int c = (t & 15) * 4;
+    float f[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (r0 + r < rows && c0 + c < cols) {
+      const float4 v = *reinterpret_cast<const float4*>(src + boff + (int64_t)(r0 + r) * cols + c0 + c);
+      f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+      if (outN) {
+        bf16_bits p[4][NP];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split_bf16<NP>(f[e], p[e]);
+#pragma unroll
+        for (int q = 0; q < NP; ++q) {
+          uint2 o;
+          o.x = p[0][q] | ((uint32_t)p[1][q] << 16);
+          o.y = p[2][q] | ((uint32_t)p[3][q] << 16);
+          *reinterpret_cast<uint2*>(outN + q * plane + boff + (int64_t)(r0 + r) * cols + c0 + c) = o;
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tile[r][c + e] = f[e];
+  }
+  if (!outT) return;
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int cl = (t >> 3) + pass * 32;
+    const int rc = (t & 7) * 8;
+    if (c0 + cl >= cols || r0 + rc >= rows) continue;
+    bf16_bits p[8][NP];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) split_bf16<NP>(tile[rc + e][cl], p[e]);
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {
+      uint4 v;
+      v.x = p[0][q] | ((uint32_t)p[1][q] << 16); v.y = p[2][q] | ((uint32_t)p[3][q] << 16);
+      v.z = p[4][q] | ((uint32_t)p[5][q] << 16); v.w = p[6][q] | ((uint32_t)p[7][q] << 16);
+      *reinterpret_cast<uint4*>(outT + q * plane + boff + (int64_t)(c0 + cl) * rows + r0 + rc) = v;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- statistics
+__global__ void __launch_bounds__(256) k_reduce_stats(const float* __restrict__ Lpart, int slabs, int64_t ldl,
+                                                      const float* __restrict__ nrm, int64_t ldn, int64_t T,
+                                                      double* __restrict__ L, unsigned long long* __restrict__ rows,
+                                                      unsigned long long* __restrict__ skipped) {
+  __shared__ double sh[4];
+  const int h = blockIdx.x;
+  double acc = 0.0, cnt = 0.0;
+  for (int64_t i = threadIdx.x; i < T; i += 256) {
+    const float n = nrm[(int64_t)h * ldn + i];
+    if (n > 0.0f) {
+      double s = 0.0;
+      for (int q = 0; q < slabs; ++q) s += (double)Lpart[((int64_t)h * slabs + q) * ldl + i];
+      acc += s / (double)n;
+      cnt += 1.0;
+    }
+  }
+  acc = block_sum_d(acc, sh);
+  cnt = block_sum_d(cnt, sh);
+  if (threadIdx.x == 0) {
+    L[h] += acc;
+    rows[h] += (unsigned long long)cnt;
+    skipped[h] += (unsigned long long)((double)T - cnt);
+  }
+}
+
+__global__ void __launch_bounds__(256) k_fro2(const float* __restrict__ M, int64_t n, double* __restrict__ fro2) {
+  __shared__ double sh[4];
+  const float* m = M + (int64_t)blockIdx.y * n;
+  double acc = 0.0;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(m + i);
+    acc += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
+  }
+  acc = block_sum_d(acc, sh);
+  if (threadIdx.x == 0) atomicAdd(fro2 + blockIdx.y, acc);
+}
+
+__global__ void __launch_bounds__(256) k_polar_start(const float* __restrict__ M, const float* __restrict__ R, int64_t n, int dh,
+                                                     float lambda, const double* __restrict__ fro2, float* __restrict__ X) {
+  const int h = blockIdx.y;
+  const double f = sqrt(fro2[h]);
+  const bool empty = !(f > 0.0);
+  // lambda = 0 is taken as the limit lambda -> 0+ at fp32 resolution: the floor ties the
+  // update to R_prev on the null space of M (where every completion is optimal) and
+  // breaks exact degeneracies (repeated columns of M) that the iteration would preserve.
+  lambda = fmaxf(lambda, 9.5367431640625e-07f);
+  const float tau = (float)(f / sqrt((double)dh));
+  const float inv_alpha = empty ? 1.0f : (float)(1.0 / (f * (1.0 + (double)lambda)));
+  const float cm = empty ? 0.0f : inv_alpha;
+  const float cr = empty ? 1.0f : lambda * tau * inv_alpha;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
+    const float4 m = *reinterpret_cast<const float4*>(M + h * n + i);
+    const float4 r = *reinterpret_cast<const float4*>(R + h * n + i);
+    float4 o;
+    o.x = cm * m.x + cr * r.x; o.y = cm * m.y + cr * r.y; o.z = cm * m.z + cr * r.z; o.w = cm * m.w + cr * r.w;
+    *reinterpret_cast<float4*>(X + h * n + i) = o;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_axpy(float* __restrict__ X, const float* __restrict__ R, int64_t n, float kappa) {
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
+    float4 x = *reinterpret_cast<float4*>(X + i);
+    const float4 r = *reinterpret_cast<const float4*>(R + i);
+    x.x += kappa * r.x; x.y += kappa * r.y; x.z += kappa * r.z; x.w += kappa * r.w;
+    *reinterpret_cast<float4*>(X + i) = x;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_polar_finish(const float* __restrict__ X, const float* __restrict__ M, int64_t n,
+                                                      float* __restrict__ R, double* __restrict__ inner) {
+  __shared__ double sh[4];
+  const int h = blockIdx.y;
+  double acc = 0.0;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
+    const float4 x = *reinterpret_cast<const float4*>(X + h * n + i);
+    const float4 m = *reinterpret_cast<const float4*>(M + h * n + i);
+    acc += (double)x.x * m.x + (double)x.y * m.y + (double)x.z * m.z + (double)x.w * m.w;
+    *reinterpret_cast<float4*>(R + h * n + i) = x;
+  }
+  acc = block_sum_d(acc, sh);
+  if (threadIdx.x == 0) atomicAdd(inner + h, acc);
+}
+
+// ---------------------------------------------------------------- fake-quantisation error
+// One workgroup per token row.  The row is read once from HBM (kept in registers
+// for d <= 8192 bf16 / 4096 fp32; longer rows re-read the tail from cache).
+template <bool F32>
+__global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y, int64_t ld, int d, float qmax,
+                                                     float* __restrict__ row_sse, float* __restrict__ row_en) {
+  constexpr int EPC = F32 ? 4 : 8;  // elements per 16-byte chunk
+  __shared__ float shm[4];
+  __shared__ double shd[4];
+  const int64_t row = blockIdx.x;
+  const int nch = d / EPC;
+  const uint4* y = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(Y) + row * ld * (F32 ? 4 : 2));
+  auto expand = [](const uint4& v, float* f) {
+    if constexpr (F32) {
+      f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    } else {
+      unpack8(v, f);
+    }
+  };
+  uint4 cache[4];
+  float amax = 0.0f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int c = threadIdx.x + 256 * q;
+    cache[q] = make_uint4(0, 0, 0, 0);
+    if (c < nch) {
+      cache[q] = y[c];
+      float f[EPC];
+      expand(cache[q], f);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));
+    }
+  }
+  for (int c = threadIdx.x + 1024; c < nch; c += 256) {
+    float f[EPC];
+    expand(y[c], f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));
+  }
+  amax = wave_max(amax);
+  if ((threadIdx.x & 63) == 0) shm[threadIdx.x >> 6] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(shm[0], shm[1]), fmaxf(shm[2], shm[3]));
+  const float delta = amax / qmax;
+  float sse = 0.0f, en = 0.0f;
+  auto score = [&](const uint4& v) {
+    float f[EPC];
+    expand(v, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      float code = 0.0f;
+      if (amax > 0.0f) code = fminf(fmaxf(rintf(f[e] / delta), -qmax), qmax);
+      const float err = fmaf(-delta, code, f[e]);
+      sse = fmaf(err, err, sse);
+      en = fmaf(f[e], f[e], en);
+    }
+  };
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if ((int)threadIdx.x + 256 * q < nch) score(cache[q]);
+  for (int c = threadIdx.x + 1024; c < nch; c += 256) score(y[c]);
+  const double s = block_sum_d((double)sse, shd);
+  const double e = block_sum_d((double)en, shd);
+  if (threadIdx.x == 0) {
+    row_sse[row] = (float)s;
+    row_en[row] = (float)e;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_sum_rows(const float* __restrict__ a, const float* __restrict__ b, int64_t T,
+                                                  double* __restrict__ out) {
+  __shared__ double sh[4];
+  double sa = 0.0, sb = 0.0;
+  for (int64_t i = threadIdx.x; i < T; i += 256) {
+    sa += (double)a[i];
+    sb += (double)b[i];
+  }
+  sa = block_sum_d(sa, sh);
+  sb = block_sum_d(sb, sh);
+  if (threadIdx.x == 0) {
+    out[0] = sa;
+    out[1] = sb;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_fill_zero(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+inline int grid_for(int64_t items, int cap = 4096) {
+  int64_t g = (items + 255) / 256;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (int)g;
+}
+
+}  // namespace
+
+hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh, float* nrm, float* w,
+                            int64_t ldn, int* nonfinite, hipStream_t s) {
+  const int64_t waves = T * heads;
+  dim3 grid((unsigned)((waves + 3) / 4));
+  if (x_is_f32)
+    hipLaunchKernelGGL(k_row_norms<true>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite);
+  else
+    hipLaunchKernelGGL(k_row_norms<false>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_scale(const void* X, int x_is_f32, int64_t T, int64_t Tk, int64_t stride, int d, int dh,
+                                  const float* w, int64_t ldn, bf16_bits* Xt, int64_t pitch, int64_t plane, int np,
+                                  hipStream_t s) {
+  dim3 grid((unsigned)(Tk / 64), (unsigned)((d + 63) / 64));
+  if (x_is_f32 && np == 3)
+    hipLaunchKernelGGL((k_transpose_scale<true, 3>), grid, dim3(256), 0, s, X, T, stride, d, dh, w, ldn, Xt, pitch, plane);
+  else if (!x_is_f32 && np == 1)
+    hipLaunchKernelGGL((k_transpose_scale<false, 1>), grid, dim3(256), 0, s, X, T, stride, d, dh, w, ldn, Xt, pitch, plane);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_split_rows(const float* X, int64_t T, int64_t stride, int d, bf16_bits* Xs, int64_t plane, hipStream_t s) {
+  const int64_t items = T * (d / 4);
+  hipLaunchKernelGGL(k_split_rows, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, X, T, stride, d, Xs, plane);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
+                       int64_t plane, hipStream_t s) {
+  dim3 grid((cols + 63) / 64, (rows + 63) / 64, batch);
+  switch (np) {
+    case 1: hipLaunchKernelGGL(k_pack<1>, grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane); break;
+    case 2: hipLaunchKernelGGL(k_pack<2>, grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane); break;
+    case 3: hipLaunchKernelGGL(k_pack<3>, grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
+                               int heads, double* L, unsigned long long* rows, unsigned long long* skipped, hipStream_t s) {
+  hipLaunchKernelGGL(k_reduce_stats, dim3(heads), dim3(256), 0, s, Lpart, slabs, ldl, nrm, ldn, T, L, rows, skipped);
+  return hipGetLastError();
+}
+
+hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s) {
+  hipLaunchKernelGGL(k_fro2, dim3(grid_for(n / 4, 1024), heads), dim3(256), 0, s, M, n, fro2);
+  return hipGetLastError();
+}
+
+hipError_t launch_polar_start(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, float* X,
+                              hipStream_t s) {
+  const int64_t n = (int64_t)dh * dh;
+  hipLaunchKernelGGL(k_polar_start, dim3(grid_for(n / 4, 2048), heads), dim3(256), 0, s, M, R, n, dh, lambda, fro2, X);
+  return hipGetLastError();
+}
+
+hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s) {
+  hipLaunchKernelGGL(k_axpy, dim3(grid_for(n / 4, 2048)), dim3(256), 0, s, X, R, n, kappa);
+  return hipGetLastError();
+}
+
+hipError_t launch_polar_finish(const float* X, const float* M, int heads, int64_t n, float* R, double* inner, hipStream_t s) {
+  hipLaunchKernelGGL(k_polar_finish, dim3(grid_for(n / 4, 1024), heads), dim3(256), 0, s, X, M, n, R, inner);
+  return hipGetLastError();
+}
+
+hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,
+                              float* row_en, double* out, hipStream_t s) {
+  const float qmax = (float)((1 << (bits - 1)) - 1);
+  if (y_is_f32)
+    hipLaunchKernelGGL(k_quant_error<true>, dim3((unsigned)T), dim3(256), 0, s, Y, ld, d, qmax, row_sse, row_en);
+  else
+    hipLaunchKernelGGL(k_quant_error<false>, dim3((unsigned)T), dim3(256), 0, s, Y, ld, d, qmax, row_sse, row_en);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(256), 0, s, row_sse, row_en, T, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 4;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_fill_zero, dim3(grid_for((int64_t)n, 2048)), dim3(256), 0, s, reinterpret_cast<uint32_t*>(p), n);
+  return hipGetLastError();
+}
+
+}  // namespace conqur
