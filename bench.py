@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the calibration hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic activation batch:
+conqur_step_batch (rotate + normalise + corner + accumulate), conqur_quant_error
+(int4 score of the rotated batch) and conqur_update_rotation (Procrustes / polar).
+Workload: c3 of the benchmark's configs -- d = 4096, bf16 activations, 2048 tokens per
+batch, one update per batch, prox_lambda = 0.1 (the cross-covariance of a 2048-token
+batch is rank deficient at d = 4096).  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+  value            tokens/s of rotate+corner+accumulate alone (the metric's first
+                   half), from HIP events around conqur_step_batch's kernels
+  ms_per_procrustes  the metric's second half: device ms per conqur_update_rotation
+  ms_per_step      wall-clock per whole step (step_batch + quant_error + update)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16/fp16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, X0, R0, sample_tokens):
+    """The oracle, as it stands, on a bounded sample: one step_batch on `sample_tokens` rows of a c3 batch."""
+    from oracle import oracle as O
+    oc = O.OracleCalibrator(w.d, w.heads, w.dtype, R0, w.prox_lambda)
+    Xs = X0[:sample_tokens]
+    t0 = time.perf_counter()
+    oc.step_batch(Xs)
+    dt = time.perf_counter() - t0
+    # Procrustes: the Jacobi SVD is O(d^3) per sweep; time it at d = 384 and scale by (4096/384)^3
+    import numpy as np
+    ds = 1024
+    A = np.random.Generator(np.random.Philox(key=1)).standard_normal((ds, ds))
+    t1 = time.perf_counter()
+    O.procrustes(A)
+    dp = time.perf_counter() - t1
+    return {
+        "value": sample_tokens / dt, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+        "sample": f"oracle step_batch (rotate+corner+accumulate, fp64 naive loops) on the first {sample_tokens} "
+                  f"tokens of batch 0 of c3 (d={w.d}), {dt:.2f} s; oracle Procrustes (one-sided Jacobi SVD) "
+                  f"timed at d={ds}: {dp:.2f} s, x (4096/{ds})^3 = {dp * (4096 / ds) ** 3:.0f} s extrapolated",
+        "procrustes_s_extrapolated_d4096": dp * (4096 / ds) ** 3,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path is single-device; see DESIGN.md for how it would "
+              "shard); --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_10793_amd import binding as B
+    from paper_2605_10793_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device", file=sys.stderr)
+        sys.exit(1)
+    w = I.WORKLOADS[args.workload]
+    T, d = w.tokens_per_batch, w.d
+    K, W = args.steps, args.warmup
+    n_distinct = min(K + W, 8)
+    host = [I.batch(w, b) for b in range(n_distinct)]
+    R0 = I.initial_rotation(w)
+    dev = [B.to_device(x, w.dtype) for x in host]
+    cal = B.Calibrator(d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
+    cal.set_timing(True)
+
+    def one_step(i):
+        X = dev[i % n_distinct]
+        cal.step_batch(X)
+        sse, en = cal.quant_error(X, 4)
+        _, st = cal.update_rotation()
+        return sse / en, st
+
+    for i in range(W):
+        one_step(i)
+    torch.cuda.synchronize()
+    acc = {k: 0.0 for k in ("prep", "rotate", "accumulate", "stats", "update", "quant_rotate", "quant_error")}
+    iters = 0
+    rel = []
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        r, st = one_step(i)
+        tm = cal.timing()           # stream is already synchronised by update_rotation
+        for k in acc:
+            acc[k] += tm[k]
+        iters += st[0]["iters"]
+        rel.append(r)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for k in acc:
+        acc[k] /= K
+    step_ms = acc["prep"] + acc["rotate"] + acc["accumulate"] + acc["stats"]
+    gemm_ms = acc["rotate"] + acc["accumulate"]
+    dh = w.dh
+    step_flops = 4.0 * T * dh * dh * w.heads            # rotate + accumulate, per batch
+    polar_flops = 4.0 * dh ** 3 * w.heads * (iters / K)  # one Gram + one apply per Newton-Schulz iteration
+    y_bytes = T * d * (2 if w.dtype == "bf16" else 4)
+    out = {
+        "metric": "calibration tokens/sec (rotate+corner+accumulate) at d=4096; ms per Procrustes",
+        "value": T / (step_ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": wall * 1e3 / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: d={d}, heads={w.heads}, {w.dtype} activations, {T} tokens/batch, one "
+                               f"Procrustes update per batch, prox_lambda={w.prox_lambda}, fp32 M and R",
+                   "tokens_per_batch": T, "d": d, "heads": w.heads},
+        "ms_per_procrustes": acc["update"],
+        "polar_iters_per_update": iters / K,
+        "end_to_end_tokens_per_s": T * K / wall,
+        "stage_ms": acc,
+        "int4_rel_err_first_last": [rel[0], rel[-1]],
+        "roofline": {
+            "bound": "mfma", "kernel": "gemm_nt_kernel (rotate+corner launch and accumulate launch of step_batch)",
+            "achieved": step_flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": step_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
+            "flops_per_launch_pair": step_flops, "ms_per_launch_pair": gemm_ms,
+        },
+        "roofline_polar": {
+            "bound": "mfma", "achieved": polar_flops / (acc["update"] * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": polar_flops / (acc["update"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "note": "algorithmic 4*d^3 per Newton-Schulz iteration over the whole update (split-precision "
+                    "iterations issue 6x the MFMA work of a bf16 one)",
+        },
+        "roofline_quant_error": {
+            "bound": "hbm", "achieved": y_bytes / (acc["quant_error"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+            "unit": "GB/s", "frac": y_bytes / (acc["quant_error"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, host[0], R0, args.cpu_sample_tokens)
+    cal.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
