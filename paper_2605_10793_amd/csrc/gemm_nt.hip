@@ -1,79 +1,160 @@
 // bf16 MFMA "NT" GEMM with fused epilogues (see gemm_nt.h).
 //
-// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of the output;
-// each 64-lane wavefront owns (BM/2) x (BN/2) as a grid of 32x32 MFMA tiles
-// (v_mfma_f32_32x32x16_bf16, fp32 accumulators).  The K loop advances 64 elements
-// per step: the next step's operand tiles are fetched from HBM/L2 into registers
-// (16-byte loads, K-contiguous) while the current step's tiles are consumed from
-// LDS, then written to the other LDS stage; one barrier per step.
+// Tiling: a workgroup of WGM x WGN wavefronts owns a BM x BN tile of the output; each
+// 64-lane wavefront owns (BM/WGM) x (BN/WGN) as a grid of 32x32 MFMA tiles
+// (v_mfma_f32_32x32x16_bf16 / _f16, fp32 accumulators).  The large tiles run 8
+// wavefronts (2 per SIMD) so that one wave's MFMAs cover the other's LDS / barrier /
+// load-issue latencies.
 //
-// LDS layout: a tile row is 64 bf16 = 128 bytes = 8 chunks of 16 bytes; chunk c of
-// row r sits at physical chunk c ^ ((r >> 1) & 7), which spreads the 16 rows a
-// ds_read_b128 quarter-wave touches over all 64 banks and keeps the 16-byte
-// row-major writes conflict free as well.
+// Operand path: HBM/L2 -> LDS directly (buffer_load ... lds, 16 bytes per lane, no
+// register staging), 4 LDS stages of 32 K-elements, fragments double buffered in
+// registers, one fence-free barrier per K step placed between MFMA groups.
+//
+// LDS layout: a tile row is 32 bf16 = 64 bytes = 4 chunks of 16 bytes; chunk c of row r
+// sits at physical chunk c ^ ((r >> 2) & 3), which spreads any 16 consecutive rows of
+// one logical chunk (what a ds_read_b128 quarter-wave touches) over all 64 banks;
+// measured SQ_LDS_BANK_CONFLICT = 0.
 #include "gemm_nt.h"
 
 namespace conqur {
 
 namespace {
 
-constexpr int BK = 64;
+constexpr int BK = 32;      // K elements per pipeline stage (one LDS tile row = 64 bytes = 4 chunks of 16 bytes)
+constexpr int NSTAGE = 4;   // LDS stages: three tiles in flight behind the one being consumed
 
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+  return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4);
 }
 
-template <int BM, int BN, int EPI, bool F16>
-__global__ void __launch_bounds__(256) gemm_nt_kernel(const GemmArgs g, const int tiles_m, const int tiles_n) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-  constexpr int PA = BM / 32, PB = BN / 32;
-  constexpr int STAGE = (BM + BN) * 128;
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = simm16[15:14]:[3:0], expcnt and lgkmcnt left at max).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier without the release/acquire fence of __syncthreads(): the fence
+// would drain every outstanding LDS-direct load (vmcnt(0)) and serialise the
+// pipeline.  Ordering here is explicit: each wave waits (vmcnt) for its own loads of
+// the tile that is consumed next, and its LDS reads of the current tile have
+// returned before its last MFMA of the step could issue.  The "memory" clobber keeps
+// the compiler from moving LDS accesses across the barrier.
+__device__ __forceinline__ void pipeline_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// K-tail / invalid-row loads are pointed past the end of the buffer descriptor, where
+// the hardware returns zeros (also for loads whose destination is LDS).
+constexpr uint32_t kOobOffset = 0x80000000u;
+
+template <int BM, int BN, int WGM, int WGN, int EPI, bool F16>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs g, const int tiles_m, const int tiles_n) {
+  constexpr int NW = WGM * WGN;                 // wavefronts per workgroup
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  constexpr int NLA = BM / 16, NLB = BN / 16;   // wave-wide 1 KiB loads per stage (16 tile rows each)
+  constexpr int QA = NLA / NW, QB = NLB / NW;   // ... per wavefront
+  static_assert(NLA % NW == 0 && NLB % NW == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+  constexpr int STAGE = (BM + BN) * 64;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
   const int half = lane >> 5, col = lane & 31;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD (own L2) a
-  // contiguous range of tiles so that neighbouring tiles share operand panels there.
+  // Workgroups are dealt round-robin to the 8 XCDs (bid % 8), each with its own L2, and
+  // an XCD runs 32 of them at a time.  Map the 32 workgroups that are co-resident on an
+  // XCD to a compact 4 x 8 block of output tiles, so that per K step the XCD pulls
+  // (4 + 8) operand panels through its L2 instead of up to (32 + 1).
   int bid = blockIdx.x;
   const int ntiles = tiles_m * tiles_n;
-  if ((ntiles & 7) == 0) bid = (bid & 7) * (ntiles >> 3) + (bid >> 3);
-  const int tm = bid % tiles_m, tn = bid / tiles_m;
+  int tm, tn;
+  if ((tiles_m & 3) == 0 && (tiles_n & 7) == 0 && (((tiles_m >> 2) * (tiles_n >> 3)) & 7) == 0) {
+    const int xcd = bid & 7, local = bid >> 3;
+    const int group = (local >> 5) * 8 + xcd, within = local & 31;
+    const int gm = tiles_m >> 2;
+    tm = (group % gm) * 4 + (within & 3);
+    tn = (group / gm) * 8 + (within >> 2);
+  } else {
+    if ((ntiles & 7) == 0) bid = (bid & 7) * (ntiles >> 3) + (bid >> 3);
+    tm = bid % tiles_m;
+    tn = bid / tiles_m;
+  }
   const int m0 = tm * BM, n0 = tn * BN;
   const int bz = blockIdx.z;
-  const bf16_bits* __restrict__ Ab = g.A + (int64_t)bz * g.batchA;
-  const bf16_bits* __restrict__ Bb = g.B + (int64_t)bz * g.batchB;
+  const bf16_bits* Ab = g.A + (int64_t)bz * g.batchA;
+  const bf16_bits* Bb = g.B + (int64_t)bz * g.batchB;
 
-  const int lc = tid & 7, lr = tid >> 3;
-  uint4 ra[PA], rb[PB];
+  // Global -> LDS without passing through registers: each buffer_load ... lds moves
+  // 64 lanes x 16 bytes = 16 tile rows into 1 KiB of LDS (lane L lands at L*16).
+  // Lane L therefore fetches the chunk that the swizzled layout stores at row L/4,
+  // physical chunk L%4.  Rows past M (N) lie past the descriptor's range and read 0.
+  const int lrow = lane >> 2, lpc = lane & 3;
+  uint32_t offA[QA], offB[QB];
+  int chunkA[QA], chunkB[QB];
+#pragma unroll
+  for (int q = 0; q < QA; ++q) {
+    const int row = (q * NW + wave) * 16 + lrow;
+    chunkA[q] = lpc ^ ((row >> 2) & 3);
+    offA[q] = (m0 + row < g.M) ? (uint32_t)(((int64_t)(m0 + row) * g.lda + chunkA[q] * 8) * 2) : kOobOffset;
+  }
+#pragma unroll
+  for (int q = 0; q < QB; ++q) {
+    const int row = (q * NW + wave) * 16 + lrow;
+    chunkB[q] = lpc ^ ((row >> 2) & 3);
+    offB[q] = (n0 + row < g.N) ? (uint32_t)(((int64_t)(n0 + row) * g.ldb + chunkB[q] * 8) * 2) : kOobOffset;
+  }
+  const uint32_t recA = (uint32_t)((((int64_t)g.M - 1) * g.lda + BK) * 2);
+  const uint32_t recB = (uint32_t)((((int64_t)g.N - 1) * g.ldb + BK) * 2);
   const int nkb = (g.K + BK - 1) / BK;
   const int nit = nkb * g.nseg;
+  const bool ktail = (g.K % BK) != 0;
+  // offsets for the last, partial K step of a segment: chunks past K read zeros
+  uint32_t offAt[QA], offBt[QB];
+  {
+    const int kleft = g.K - (nkb - 1) * BK;
+#pragma unroll
+    for (int q = 0; q < QA; ++q) offAt[q] = (chunkA[q] * 8 < kleft) ? offA[q] : kOobOffset;
+#pragma unroll
+    for (int q = 0; q < QB; ++q) offBt[q] = (chunkB[q] * 8 < kleft) ? offB[q] : kOobOffset;
+  }
 
-  auto gload = [&](int it) {
-    const int s = it / nkb, kb = it - s * nkb;
-    const int k = kb * BK + lc * 8;
-    const bool kok = k < g.K;
-    const bf16_bits* As = Ab + g.a_seg[s] + k;
-    const bf16_bits* Bs = Bb + g.b_seg[s] + k;
-#pragma unroll
-    for (int p = 0; p < PA; ++p) {
-      const int m = m0 + p * 32 + lr;
-      ra[p] = (kok && m < g.M) ? *reinterpret_cast<const uint4*>(As + (int64_t)m * g.lda) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int p = 0; p < PB; ++p) {
-      const int n = n0 + p * 32 + lr;
-      rb[p] = (kok && n < g.N) ? *reinterpret_cast<const uint4*>(Bs + (int64_t)n * g.ldb) : make_uint4(0, 0, 0, 0);
+  // Issue state: the next tile to fetch is K step is_kb of segment is_s; its operand
+  // pointers advance incrementally (wave-uniform, scalar registers).
+  int is_s = 0, is_kb = 0;
+  const bf16_bits* pa = Ab + g.a_seg[0];
+  const bf16_bits* pb = Bb + g.b_seg[0];
+  __amdgpu_buffer_rsrc_t ra, rb;
+  bool tail = false;
+  auto issue_prep = [&]() {
+    // Past the last tile the pipeline keeps issuing (so that every step has the same
+    // number of loads in flight and needs no branches); those loads get an empty
+    // descriptor range, fetch nothing and write zeros to a stage nobody reads again.
+    const bool real = is_s < g.nseg;
+    ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_bits*>(pa), 0, real ? recA : 0u, 0x00020000);
+    rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_bits*>(pb), 0, real ? recB : 0u, 0x00020000);
+    tail = ktail && is_kb == nkb - 1;
+    if (++is_kb == nkb) {
+      is_kb = 0;
+      ++is_s;
+      const int sc = is_s < g.nseg ? is_s : g.nseg - 1;
+      pa = Ab + g.a_seg[sc];
+      pb = Bb + g.b_seg[sc];
+    } else {
+      pa += BK; pb += BK;
     }
   };
-  auto lstore = [&](int stage) {
+  auto issue_one = [&](int q, int stage) {   // load q of LPT of the prepared tile
     unsigned char* sa = smem + stage * STAGE;
-    unsigned char* sb = sa + BM * 128;
-#pragma unroll
-    for (int p = 0; p < PA; ++p) *reinterpret_cast<uint4*>(sa + lds_off(p * 32 + lr, lc)) = ra[p];
-#pragma unroll
-    for (int p = 0; p < PB; ++p) *reinterpret_cast<uint4*>(sb + lds_off(p * 32 + lr, lc)) = rb[p];
+    if (q < QA) {
+      const uint32_t off = tail ? offAt[q] : offA[q];
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(sa + (q * NW + wave) * 1024), 16,
+                                               off, 0, 0, 0);
+    } else {
+      const int qb = q - QA;
+      const uint32_t off = tail ? offBt[qb] : offB[qb];
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sa + BM * 64 + (qb * NW + wave) * 1024),
+                                               16, off, 0, 0, 0);
+    }
   };
 
   f32x16 acc[TM][TN];
@@ -84,36 +165,87 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(const GemmArgs g, const in
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int it = 0; it < nit; ++it) {
-    const int cur = it & 1;
-    if (it + 1 < nit) gload(it + 1);
-    const unsigned char* sa = smem + cur * STAGE;
-    const unsigned char* sb = sa + BM * 128;
+  // Software pipeline.  LDS holds NSTAGE tiles; tile t lives in stage t % NSTAGE.
+  // Operand fragments are double buffered in registers: while the MFMAs of K-substep
+  // kk run, the fragments of substep kk+1 are read from LDS (one ds_read per MFMA, so
+  // the reads issue in the MFMA's shadow).  The step's only synchronisation sits in the
+  // middle of its last substep: wait for this wave's loads of the next tile (vmcnt
+  // counts outstanding loads, which retire in order), barrier (now every wave's part of
+  // the next tile is visible and every wave has finished reading the current stage),
+  // refill the current stage with tile it+NSTAGE, read the first fragments of the next
+  // tile, and cover that latency with the second half of the substep's MFMAs.
+  constexpr int LPT = QA + QB;   // loads per thread per tile
+  constexpr int KS = BK / 16;    // MFMA K-substeps per tile
+  constexpr int NMF = TM * TN;
+  static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of substeps");
+  bf16x8 fa[2][TM], fb[2][TN];
+
+  auto read_frag = [&](int buf, int r, const unsigned char* sa, int kk) {
+    // read number r of a substep, in the order the MFMAs need them: a0, b0..b(TN-1), a1..a(TM-1)
+    const unsigned char* sb = sa + BM * 64;
+    if (r == 0) fa[buf][0] = *reinterpret_cast<const bf16x8*>(sa + lds_off(wm * WM + col, kk * 2 + half));
+    else if (r <= TN) fb[buf][r - 1] = *reinterpret_cast<const bf16x8*>(sb + lds_off(wn * WN + (r - 1) * 32 + col, kk * 2 + half));
+    else fa[buf][r - TN] = *reinterpret_cast<const bf16x8*>(sa + lds_off(wm * WM + (r - TN) * 32 + col, kk * 2 + half));
+  };
+  auto mfma = [&](int buf, int m) {
+    const int i = m / TN, j = m % TN;
+    if constexpr (F16)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[buf][i]), __builtin_bit_cast(f16x8, fb[buf][j]),
+                                                         acc[i][j], 0, 0, 0);
+    else
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
+
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[TM], bfr[TN];
+  for (int p = 0; p < NSTAGE; ++p) {
+    issue_prep();
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(sa + lds_off(wm * WM + i * 32 + col, kk * 2 + half));
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(sb + lds_off(wn * WN + j * 32 + col, kk * 2 + half));
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          if constexpr (F16)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, af[i]), __builtin_bit_cast(f16x8, bfr[j]),
-                                                               acc[i][j], 0, 0, 0);
-          else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (it + 1 < nit) lstore(cur ^ 1);
-    __syncthreads();
+    for (int q = 0; q < LPT; ++q) issue_one(q, p);
   }
+  wait_vmcnt<(NSTAGE - 1) * LPT>();   // tile 0 has landed
+  pipeline_barrier();
+#pragma unroll
+  for (int r = 0; r < TM + TN; ++r) read_frag(0, r, smem, 0);
+
+  for (int it = 0; it < nit; ++it) {
+    const int stage = it % NSTAGE;
+    const unsigned char* sa = smem + stage * STAGE;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < KS) {
+#pragma unroll
+        for (int m = 0; m < NMF; ++m) {
+          mfma(cur, m);
+          if (m < TM + TN) read_frag(nxt, m, sa, kk + 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int r = NMF; r < TM + TN; ++r) read_frag(nxt, r, sa, kk + 1);
+      } else {
+        issue_prep();   // tile it+NSTAGE refills the stage being consumed; scalar work, hidden behind the MFMAs
+#pragma unroll
+        for (int m = 0; m < NMF / 2; ++m) mfma(cur, m);
+        __builtin_amdgcn_sched_barrier(0);
+        // tiles up to it+NSTAGE-1 have been issued; all but the newest NSTAGE-2 have landed => tile it+1 is in LDS
+        wait_vmcnt<(NSTAGE - 2) * LPT>();
+        pipeline_barrier();
+        const unsigned char* sn = smem + ((it + 1) % NSTAGE) * STAGE;
+#pragma unroll
+        for (int r = 0; r < TM + TN; ++r) read_frag(nxt, r, sn, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = NMF / 2; m < NMF; ++m) {
+          mfma(cur, m);
+          if (m - NMF / 2 < LPT) issue_one(m - NMF / 2, stage);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = NMF - NMF / 2; q < LPT; ++q) issue_one(q, stage);
+      }
+    }
+  }
+  wait_vmcnt<0>();   // drain the padding loads before the epilogue reuses nothing of LDS (keeps exit clean)
 
   // Accumulator element e = 4*j + i of tile (im, in) is output row
   //   m = m0 + wm*WM + im*32 + 8*j + 4*half + i,   column n = n0 + wn*WN + in*32 + col.
@@ -121,9 +253,9 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(const GemmArgs g, const in
 
   if constexpr (EPI == EPI_SIGN) {
     bf16_bits* St = reinterpret_cast<bf16_bits*>(g.C) + (int64_t)bz * g.batchC;
-    const int slabs = tiles_n * 2;
+    const int slabs = tiles_n * WGN;
     const uint32_t one = g.sign_f16 ? 0x3C00u : 0x3F80u;
-    float* Lp = g.Lpart + ((int64_t)bz * slabs + tn * 2 + wn) * g.ldl;
+    float* Lp = g.Lpart + ((int64_t)bz * slabs + tn * WGN + wn) * g.ldl;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       float rs[16];
@@ -220,13 +352,14 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(const GemmArgs g, const in
   }
 }
 
-struct Tile { int bm, bn; float eff; };
-constexpr Tile kTiles[] = {{256, 256, 1.0f}, {256, 128, 0.9f}, {128, 128, 0.75f}, {64, 64, 0.4f}};
+struct Tile { int bm, bn, wgm, wgn; float eff; };
+constexpr Tile kTiles[] = {{256, 256, 2, 4, 1.0f}, {256, 128, 4, 2, 0.85f}, {128, 128, 2, 2, 0.7f}, {64, 64, 2, 2, 0.35f}};
+constexpr int kNumTiles = 4;
 
 int pick_tile(int M, int N, int batch) {
   int best = 0;
   double best_cost = 1e300;
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < kNumTiles; ++t) {
     const int64_t tiles = (int64_t)((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn) * batch;
     const int64_t waves = (tiles + 255) / 256;
     const double cost = (double)waves * kTiles[t].bm * kTiles[t].bn / kTiles[t].eff;
@@ -235,11 +368,11 @@ int pick_tile(int M, int N, int batch) {
   return best;
 }
 
-template <int BM, int BN, int EPI, bool F16>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool F16>
 hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
-  constexpr int smem = 2 * (BM + BN) * 128;
+  constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
-  auto kern = gemm_nt_kernel<BM, BN, EPI, F16>;
+  auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, EPI, F16>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -247,17 +380,17 @@ hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
   }
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, 1, batch);
-  hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, a, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), smem, stream, a, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
 template <int EPI, bool F16 = false>
 hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
   switch (pick_tile(a.M, a.N, batch)) {
-    case 0: return launch_one<256, 256, EPI, F16>(a, batch, stream);
-    case 1: return launch_one<256, 128, EPI, F16>(a, batch, stream);
-    case 2: return launch_one<128, 128, EPI, F16>(a, batch, stream);
-    default: return launch_one<64, 64, EPI, F16>(a, batch, stream);
+    case 0: return launch_one<256, 256, 2, 4, EPI, F16>(a, batch, stream);
+    case 1: return launch_one<256, 128, 4, 2, EPI, F16>(a, batch, stream);
+    case 2: return launch_one<128, 128, 2, 2, EPI, F16>(a, batch, stream);
+    default: return launch_one<64, 64, 2, 2, EPI, F16>(a, batch, stream);
   }
 }
 
@@ -265,12 +398,12 @@ hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
 
 int gemm_sign_slabs(int M, int N, int batch) {
   const Tile& t = kTiles[pick_tile(M, N, batch)];
-  return 2 * ((N + t.bn - 1) / t.bn);
+  return t.wgn * ((N + t.bn - 1) / t.bn);
 }
 
 hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStream_t stream) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
-      batch < 1 || (a.ab_f16 && epi != EPI_F32))
+      batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
     return hipErrorInvalidValue;
   switch (epi) {
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
