@@ -53,8 +53,13 @@ typedef struct {
   float prox_lambda;        /* 0: R <- polar(M), the paper's update (Sec. 3.3).  > 0: R <- polar(M +
                                lambda * tau * R_prev), tau = ||M||_F / sqrt(dh): the proximal reading
                                that makes the update unique when M is rank deficient               */
-  float polar_tol;          /* stop when ||X^T X - I||_F <= tol; 0 selects 5e-5                      */
+  float polar_tol;          /* stop when ||X^T X - I||_F <= tol; 0 selects 8e-5                      */
   uint32_t polar_max_iters; /* 0 selects 200                                                        */
+  uint32_t polar_precision; /* arithmetic of the main polar iterations: 0 = single bf16 operands (fast;
+                               meets the orthogonality and objective tolerances, R itself deviates on
+                               directions with small singular values), 1 = two bf16 planes per operand
+                               (about 16 significant bits), 2 = three planes (fp32-equivalent products).
+                               The closing iterations always run fp32-equivalent.                     */
   int32_t device;           /* HIP device ordinal                                                   */
   void* stream;             /* hipStream_t the caller owns (NULL = the device's default stream)      */
 } conqur_config;
@@ -69,8 +74,8 @@ typedef struct {
 
 /* Per-head result of one Procrustes update (HOST struct). */
 typedef struct {
-  uint32_t iters;       /* polar iterations run (cheap + accurate)                                 */
-  uint32_t accurate;    /* how many of them ran in split (fp32-equivalent) arithmetic              */
+  uint32_t iters;       /* polar iterations run (main + closing)                                   */
+  uint32_t accurate;    /* how many of them were closing iterations (fp32-equivalent Gram)         */
   double orth_err;      /* ||R^T R - I||_F of the stored fp32 R, as measured on the device          */
   double inner;         /* <R_new, M>, the Procrustes objective value (nuclear norm at the optimum)  */
   double m_fro;         /* ||M||_F                                                                  */

@@ -30,7 +30,8 @@ EXPORTS = [
 class Config(ctypes.Structure):
     _fields_ = [("d", ctypes.c_uint32), ("heads", ctypes.c_uint32), ("act_dtype", ctypes.c_uint32),
                 ("max_tokens", ctypes.c_uint32), ("prox_lambda", ctypes.c_float), ("polar_tol", ctypes.c_float),
-                ("polar_max_iters", ctypes.c_uint32), ("device", ctypes.c_int32), ("stream", ctypes.c_void_p)]
+                ("polar_max_iters", ctypes.c_uint32), ("polar_precision", ctypes.c_uint32),
+                ("device", ctypes.c_int32), ("stream", ctypes.c_void_p)]
 
 
 class BatchStats(ctypes.Structure):
@@ -96,7 +97,7 @@ class Calibrator:
     """One context: `heads` rotations of width d/heads, their statistics and workspaces."""
 
     def __init__(self, d: int, heads: int, dtype: str, R0: np.ndarray, max_tokens: int,
-                 prox_lambda: float = 0.0, polar_tol: float = 0.0, polar_max_iters: int = 0,
+                 prox_lambda: float = 0.0, polar_tol: float = 0.0, polar_max_iters: int = 0, polar_precision: int = 0,
                  device: int = 0, stream: Optional[int] = None):
         import torch
         self._lib = load()
@@ -104,7 +105,7 @@ class Calibrator:
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
         cfg = Config(d, heads, BF16 if dtype == "bf16" else F32, max_tokens, prox_lambda, polar_tol,
-                     polar_max_iters, device, ctypes.c_void_p(stream))
+                     polar_max_iters, polar_precision, device, ctypes.c_void_p(stream))
         R0 = np.ascontiguousarray(R0, dtype=np.float32)
         if R0.size != heads * self.dh * self.dh:
             raise ValueError("R0 must hold heads * dh * dh floats")

@@ -22,8 +22,11 @@ namespace {
 // of the left operand with plane b of the right one; smallest terms first.
 struct SegList { int n; int a[kMaxSegments]; int b[kMaxSegments]; };
 constexpr SegList kSeg1 = {1, {0}, {0}};
+constexpr SegList kSeg3 = {3, {1, 0, 0}, {0, 1, 0}};                     // two planes each: hi*hi + hi*lo + lo*hi
 constexpr SegList kSeg6 = {6, {2, 1, 0, 1, 0, 0}, {0, 1, 2, 0, 1, 0}};  // all terms down to 2^-24 relative
 constexpr SegList kSeg3x1 = {3, {2, 1, 0}, {0, 0, 0}};                   // 3-plane left operand, exact right operand
+
+constexpr int kResidSlots = 512;
 
 enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_COUNT };
 
@@ -55,9 +58,12 @@ struct conqur_ctx {
   float *row_sse = nullptr, *row_en = nullptr;
   double* qsum = nullptr;      // [2]
   // polar workspaces
-  float *PX = nullptr, *PP = nullptr;              // iterate and polynomial factor, fp32
-  bf16_bits *PXn = nullptr, *PXt = nullptr, *PPn = nullptr;  // [3][heads][dh][dh] split planes
-  double *resid = nullptr, *fro2 = nullptr, *inner = nullptr;  // [heads]
+  float* PX = nullptr;                               // polar iterate, fp32 [heads][dh][dh]
+  bf16_bits *PXn[2] = {nullptr, nullptr};            // iterate as bf16 split planes [3][heads][dh][dh], ping-pong
+  bf16_bits *PXt[2] = {nullptr, nullptr};            // ... transposed
+  bf16_bits* PW = nullptr;                           // polynomial factor planes [3][heads][dh][dh]
+  double* resid = nullptr;                           // [kResidSlots][heads] residual history of one update
+  double *fro2 = nullptr, *inner = nullptr;          // [heads]
   int64_t last_T = 0;
 
   bool timing = false;
@@ -162,7 +168,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   const uint32_t dh = cfg->d / cfg->heads;
   if (dh % 16 || dh > 8192 || cfg->d > 65536) return CONQUR_EINVAL;
   if (cfg->act_dtype != CONQUR_F32 && cfg->act_dtype != CONQUR_BF16) return CONQUR_EINVAL;
-  if (cfg->max_tokens == 0 || cfg->max_tokens > (1u << 22)) return CONQUR_EINVAL;
+  if (cfg->max_tokens == 0 || cfg->max_tokens > (1u << 22) || cfg->polar_precision > 2) return CONQUR_EINVAL;
   if (!(cfg->prox_lambda >= 0.0f) || !(cfg->polar_tol >= 0.0f)) return CONQUR_EINVAL;
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return CONQUR_EHIP;
@@ -171,7 +177,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   conqur_ctx* ctx = new (std::nothrow) conqur_ctx();
   if (!ctx) return CONQUR_ENOMEM;
   ctx->cfg = *cfg;
-  if (ctx->cfg.polar_tol == 0.0f) ctx->cfg.polar_tol = 5e-5f;
+  if (ctx->cfg.polar_tol == 0.0f) ctx->cfg.polar_tol = 8e-5f;
   if (ctx->cfg.polar_max_iters == 0) ctx->cfg.polar_max_iters = 200;
   ctx->d = (int)cfg->d; ctx->heads = (int)cfg->heads; ctx->dh = (int)dh;
   ctx->f32 = cfg->act_dtype == CONQUR_F32;
@@ -204,11 +210,12 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   A(dev_alloc(ctx, &ctx->row_en, tmax));
   A(dev_alloc(ctx, &ctx->qsum, (size_t)2));
   A(dev_alloc(ctx, &ctx->PX, blk));
-  A(dev_alloc(ctx, &ctx->PP, blk));
-  A(dev_alloc(ctx, &ctx->PXn, 3 * blk));
-  A(dev_alloc(ctx, &ctx->PXt, 3 * blk));
-  A(dev_alloc(ctx, &ctx->PPn, 3 * blk));
-  A(dev_alloc(ctx, &ctx->resid, (size_t)ctx->heads));
+  for (int b = 0; b < 2; ++b) {
+    A(dev_alloc(ctx, &ctx->PXn[b], 3 * blk));
+    A(dev_alloc(ctx, &ctx->PXt[b], 3 * blk));
+  }
+  A(dev_alloc(ctx, &ctx->PW, 3 * blk));
+  A(dev_alloc(ctx, &ctx->resid, (size_t)kResidSlots * ctx->heads));
   A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
   A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
   for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
@@ -307,6 +314,27 @@ conqur_status conqur_get_batch_stats(conqur_ctx* ctx, conqur_batch_stats* out) {
   return CONQUR_OK;
 }
 
+// One step polynomial p(x) = a x + b x^3 for singular values in [l, u].
+// Shape: f(x) = 1.5 (x/q) - 0.5 (x/q)^3, which peaks (value 1) at x = q.  The
+// equal-ripple choice (f(l) = f(u), q^2 = (u^2 + u l + l^2)/3) grows small values
+// fastest, but for l << u it sends the LARGEST singular values to the bottom of the
+// range, where low-precision rounding then perturbs exactly the directions that
+// carry the Procrustes objective.  So q is kept >= u / 1.532, which bounds
+// f(u) >= 0.5: the leading directions never fall below half of the current maximum
+// (growth of small values 2.30 instead of 2.60 per step).  Scaled so that the image
+// of [l, u] is [1 - E, 1 + E]; returns E.  For l = u = 1: the Newton-Schulz step.
+static double step_cubic(double l, double u, double* a, double* b) {
+  const double s = u * u + u * l + l * l;
+  const double t = std::min(u * std::sqrt(3.0 / s), 1.532);
+  const double q = u / t;
+  auto f = [q](double x) { return 1.5 * (x / q) - 0.5 * (x / q) * (x / q) * (x / q); };
+  const double lo = std::min(f(l), f(u));
+  const double c = 2.0 / (1.0 + lo);
+  *a = c * 1.5 / q;
+  *b = -c * 0.5 / (q * q * q);
+  return (1.0 - lo) / (1.0 + lo);
+}
+
 conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) {
   if (!ctx) return CONQUR_EINVAL;
   if (!ctx->have_rows) return fail(ctx, CONQUR_ESTATE, "update_rotation: no rows accumulated since the last update");
@@ -315,77 +343,142 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   const int h = ctx->heads, dh = ctx->dh;
   const int64_t blk = (int64_t)dh * dh, plane = (int64_t)h * blk;
   const bool timed = ctx->timing || out;
+  const bool trace = std::getenv("CONQUR_TRACE") != nullptr;
   if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][0], s));
 
   HIP_TRY(launch_fill_zero(ctx->fro2, h * sizeof(double), s));
   HIP_TRY(launch_fill_zero(ctx->inner, h * sizeof(double), s));
+  HIP_TRY(launch_fill_zero(ctx->resid, (size_t)kResidSlots * h * sizeof(double), s));
   HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->fro2, s));
+  // X0 = (M + lambda tau R) / alpha, alpha = ||M||_F (1 + lambda) >= ||X0||_2
   HIP_TRY(launch_polar_start(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, ctx->PX, s));
 
-  auto seg_fill = [&](GemmArgs& g, const SegList& sl) {
-    g.nseg = sl.n;
-    for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
-  };
-  std::vector<double> resid(h);
-  // Newton-Schulz: X <- X (1.5 I - 0.5 X^T X).  Cheap iterations use single bf16
-  // planes; once the residual is at the bf16 floor the iteration switches to
-  // 3-plane splits (fp32-equivalent products) until ||X^T X - I||_F <= tol.
+  const int np_main = 1 + (int)ctx->cfg.polar_precision;
+  const SegList& seg_main = np_main == 1 ? kSeg1 : (np_main == 2 ? kSeg3 : kSeg6);
+  const uint32_t cap = ctx->cfg.polar_max_iters;
   const double tol = ctx->cfg.polar_tol;
-  const double switch_at = std::sqrt((double)dh) / 128.0;
-  bool accurate = false, converged = false;
-  const bool trace = std::getenv("CONQUR_TRACE") != nullptr;
-  uint32_t iters = 0, acc_iters = 0;
-  double res_max = 0.0, prev_res = 1e300, best_res = 1e300;
-  int since_best = 0, kicks = 0;
-  for (uint32_t it = 0; it <= ctx->cfg.polar_max_iters; ++it) {
-    const int np = accurate ? 3 : 1;
-    const SegList& sl = accurate ? kSeg6 : kSeg1;
-    HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np, ctx->PXn, ctx->PXt, plane, s));
-    HIP_TRY(launch_fill_zero(ctx->resid, h * sizeof(double), s));
+  int cur = 0;            // which ping-pong plane buffer holds the iterate
+  int slot = 0;           // next residual-history slot
+  uint32_t iters = 0, closing = 0;
+
+  auto gram = [&](const SegList& sl, float ci, float cg, int np_w) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
-    g.A = ctx->PXt; g.B = ctx->PXt; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.A = ctx->PXt[cur]; g.B = ctx->PXt[cur]; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
     g.M = g.N = g.K = dh;
-    seg_fill(g, sl);
-    g.C = ctx->PP; g.ldc = dh; g.batchC = blk; g.resid = ctx->resid; g.coef_i = 1.5f; g.coef_g = -0.5f;
-    HIP_TRY(launch_gemm_nt(g, EPI_GRAM, h, s));
-    HIP_TRY(hipMemcpyAsync(resid.data(), ctx->resid, h * sizeof(double), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    res_max = 0.0;
-    for (int q = 0; q < h; ++q) res_max = std::max(res_max, std::sqrt(resid[q]));
-    if (!std::isfinite(res_max)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
-    if (trace) std::fprintf(stderr, "[conqur] polar it=%u mode=%s resid_F=%.6e\n", it, accurate ? "split3" : "bf16", res_max);
-    if (accurate && res_max <= tol) { converged = true; break; }
-    if (!accurate && (res_max <= switch_at || (res_max < 0.45 && res_max > 0.7 * prev_res))) {
-      accurate = true;   // redo this Gram in split arithmetic before applying it
-      prev_res = 1e300;
-      continue;
-    }
-    if (it == ctx->cfg.polar_max_iters) break;
-    prev_res = res_max;
-    // A singular value that is exactly zero together with an exact symmetry of M (e.g.
-    // two identical columns, which identical corner-sign columns produce) is preserved
-    // by the iteration, rounding included.  After a long plateau, nudge the iterate
-    // towards the previous rotation: on the stuck directions every completion is
-    // optimal, and this one is the nearest to R_prev.
-    if (res_max < 0.999 * best_res) { best_res = res_max; since_best = 0; }
-    else if (res_max > 0.45 && ++since_best >= 40 && kicks < 3) {
-      HIP_TRY(launch_axpy(ctx->PX, ctx->R, plane, 1.0f / 256.0f, s));
-      ++kicks; since_best = 0; best_res = 1e300;
-      continue;
-    }
-    HIP_TRY(launch_pack(ctx->PP, h, dh, dh, np, ctx->PPn, nullptr, plane, s));
+    g.nseg = sl.n;
+    for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
+    g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW; g.np_out = np_w; g.plane_out = plane;
+    g.resid = ctx->resid + (size_t)slot * h; g.coef_i = ci; g.coef_g = cg;
+    return launch_gemm_nt(g, EPI_GRAMW, h, s);
+  };
+  // X' = X W (+ X): reads the planes in buffer `cur`, writes np_x planes (both layouts)
+  // into the other buffer, and the fp32 iterate when asked.
+  auto apply = [&](const SegList& sl, int np_x, bool add_x, bool write_f32) -> hipError_t {
+    GemmArgs g;
     std::memset(&g, 0, sizeof(g));
-    g.A = ctx->PXn; g.B = ctx->PPn; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.A = ctx->PXn[cur]; g.B = ctx->PW; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
     g.M = g.N = g.K = dh;
-    seg_fill(g, sl);
-    g.C = ctx->PX; g.ldc = dh; g.batchC = blk; g.accumulate = 0;
-    HIP_TRY(launch_gemm_nt(g, EPI_F32, h, s));
-    ++iters;
-    if (accurate) ++acc_iters;
+    g.nseg = sl.n;
+    for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
+    g.ldc = dh; g.batchC = blk; g.np_out = np_x; g.plane_out = plane;
+    g.Pn = ctx->PXn[cur ^ 1]; g.Pt = ctx->PXt[cur ^ 1];
+    g.Xadd = add_x ? ctx->PX : nullptr;
+    g.C32 = write_f32 ? ctx->PX : nullptr;
+    hipError_t e = launch_gemm_nt(g, EPI_XOUT, h, s);
+    cur ^= 1;
+    return e;
+  };
+  std::vector<double> hist((size_t)kResidSlots * h);
+  auto read_resid = [&](int sl_idx, double* worst) -> conqur_status {
+    HIP_TRY(hipMemcpyAsync(hist.data() + (size_t)sl_idx * h, ctx->resid + (size_t)sl_idx * h, h * sizeof(double),
+                           hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    double w = 0.0;
+    for (int q = 0; q < h; ++q) w = std::max(w, std::sqrt(hist[(size_t)sl_idx * h + q]));
+    *worst = w;
+    return CONQUR_OK;
+  };
+
+  // ---- main phase: composed cubics X <- X (a I + b X^T X) (see step_cubic), no host round trips.
+  // The singular values of X0 lie in [l, 1]; l is the value the proximal term guarantees
+  // on the null space of M, halved.  (Smaller ones still grow by the factor a > 2.5 per
+  // step and are finished by the closing iterations.)
+  auto main_phase = [&](double l0) -> conqur_status {
+    HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s));
+    const double e_stop = np_main == 1 ? 4e-3 : 5e-4;   // the safety margins below floor the ripple near 2e-4
+    double l = l0, u = 1.0;
+    for (int k = 0; k < 64 && iters < cap && slot < kResidSlots - 8; ++k) {
+      double a, b;
+      const double E = step_cubic(l, u, &a, &b);
+      const bool last = E <= e_stop || iters + 1 >= cap;
+      HIP_TRY(gram(seg_main, (float)a, (float)b, np_main));
+      ++slot;
+      // the last main step hands over to the closing iterations: fp32 iterate + 2 planes
+      HIP_TRY(apply(seg_main, last ? std::max(np_main, 2) : np_main, false, last));
+      ++iters;
+      if (trace) std::fprintf(stderr, "[conqur] polar main step %d: [l,u]=[%.3e,%.3f] a=%.4f b=%.4f ripple=%.3e planes=%d\n", k, l, u, a, b, E, np_main);
+      if (last) break;
+      l = 0.98 * (1.0 - E);   // safety margins against rounding
+      u = 1.01 * (1.0 + E);
+    }
+    return CONQUR_OK;
+  };
+  const double lam_eff = std::max((double)ctx->cfg.prox_lambda, 9.5367431640625e-07);
+  conqur_status st = main_phase(0.5 * lam_eff / ((1.0 + lam_eff) * std::sqrt((double)dh)));
+  if (st != CONQUR_OK) return st;
+
+  // ---- closing iterations: Newton-Schulz steps X <- X + X (I - X^T X)/2 with the Gram
+  // matrix in fp32-equivalent arithmetic; the correction is small, so two planes per
+  // operand suffice for the product and the fp32 iterate is added in the epilogue.
+  bool converged = false;
+  int kicks = 0;
+  double res = 0.0;
+  int last_slot = 0;
+  if (np_main == 1 && iters < cap) {
+    // at the bf16 floor the first closing step needs only a two-plane Gram matrix
+    HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2)); ++slot;
+    HIP_TRY(apply(kSeg3, 3, true, true));
+    ++iters; ++closing;
+  } else {
+    HIP_TRY(launch_pack(ctx->PX, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
   }
+  while (true) {
+    HIP_TRY(gram(kSeg6, 0.5f, -0.5f, 2));
+    last_slot = slot++;
+    st = read_resid(last_slot, &res);
+    if (st != CONQUR_OK) return st;
+    if (trace) std::fprintf(stderr, "[conqur] polar closing check: resid_F=%.6e (iters %u)\n", res, iters);
+    if (!std::isfinite(res)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
+    if (res <= tol) { converged = true; break; }
+    if (iters >= cap || slot >= kResidSlots - 8) break;
+    if (res > 0.45 && kicks < 2 && iters + 8 < cap) {
+      // Some singular value is still (near) zero: either far below the assumed bound or
+      // pinned there by an exact symmetry of M (identical columns, which identical
+      // corner-sign columns produce and which the iteration, rounding included,
+      // preserves).  Nudge the iterate towards the previous rotation -- on those
+      // directions every completion is optimal and this one is nearest to R_prev --
+      // and run the main phase again from the nudge's scale.
+      const double kappa = np_main == 1 ? 1.0 / 64.0 : 1.0 / 256.0;
+      HIP_TRY(launch_axpy(ctx->PX, ctx->R, plane, (float)kappa, s));
+      ++kicks;
+      st = main_phase(0.25 * kappa / std::sqrt((double)dh));
+      if (st != CONQUR_OK) return st;
+      if (np_main == 1 && iters < cap) {
+        HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2)); ++slot;
+        HIP_TRY(apply(kSeg3, 3, true, true));
+        ++iters; ++closing;
+      } else {
+        HIP_TRY(launch_pack(ctx->PX, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
+      }
+      continue;
+    }
+    HIP_TRY(apply(kSeg3, 3, true, true));
+    ++iters; ++closing;
+  }
+
   HIP_TRY(launch_polar_finish(ctx->PX, ctx->M, h, blk, ctx->R, ctx->inner, s));
-  conqur_status st = refresh_operand(ctx);
+  st = refresh_operand(ctx);
   if (st != CONQUR_OK) return st;
   // statistics restart empty (Alg. 1): M is overwritten by the next accumulate
   HIP_TRY(launch_fill_zero(ctx->L, h * sizeof(double), s));
@@ -406,8 +499,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     float ms = 0.0f;
     HIP_TRY(hipEventElapsedTime(&ms, ctx->ev[ST_UPDATE][0], ctx->ev[ST_UPDATE][1]));
     for (int q = 0; q < h; ++q) {
-      out[q].iters = iters; out[q].accurate = acc_iters;
-      out[q].orth_err = std::sqrt(resid[q]);
+      out[q].iters = iters; out[q].accurate = closing;
+      out[q].orth_err = std::sqrt(hist[(size_t)last_slot * h + q]);
       out[q].inner = inner[q]; out[q].m_fro = std::sqrt(fro2[q]); out[q].ms = ms;
     }
   }

@@ -14,7 +14,10 @@ enum GemmEpilogue : int {
   EPI_SIGN = 0,  // corner signs, transposed: St[n][m] = +-1 (bf16), and per-row sum_n |acc| partials
   EPI_ACT = 1,   // Y[m][n] = acc, stored as bf16 or fp32 (rotated activations for the quantiser score)
   EPI_F32 = 2,   // C[m][n] = acc (+ C[m][n] if accumulate), fp32
-  EPI_GRAM = 3,  // P[m][n] = coef_i*[m==n] + coef_g*acc (fp32) and resid += sum (acc - [m==n])^2
+  EPI_GRAMW = 3, // acc = Gram matrix G: W = coef_i*I + coef_g*G written as np_out bf16 split planes
+                 // (natural layout) and resid += sum (G - I)^2
+  EPI_XOUT = 4,  // acc = X' (+ Xadd): written as fp32 (C32) and/or np_out bf16 split planes in natural (Pn)
+                 // and transposed (Pt) layout -- the operands of the next Gram / apply GEMMs
 };
 
 constexpr int kMaxSegments = 6;
@@ -30,16 +33,22 @@ struct GemmArgs {
   int64_t a_seg[kMaxSegments];  // element offsets of each K-segment
   int64_t b_seg[kMaxSegments];
   // epilogue
-  void* C;                 // EPI_SIGN: bf16 St; EPI_ACT: bf16/f32 Y; EPI_F32 / EPI_GRAM: fp32
-  int64_t ldc, batchC;
+  void* C;                 // EPI_SIGN: bf16 St; EPI_ACT: bf16/f32 Y; EPI_F32: fp32
+  int64_t ldc, batchC;     // pitch / batch offset of every output of the epilogue (elements)
   int c_is_f32;            // EPI_ACT: element type of C
   int accumulate;          // EPI_F32: add to C instead of overwriting
   int64_t st_rows_valid;   // EPI_SIGN: St rows hold this many m entries (padded pitch), multiple of 4
   int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
   float* Lpart;            // EPI_SIGN: [batch][slabs][ldl] partial sums of |acc| over the slab's columns
   int64_t ldl;             //           slabs = 2 * tiles_n
-  double* resid;           // EPI_GRAM: [batch] sum of squares of (acc - I)
-  float coef_i, coef_g;    // EPI_GRAM
+  double* resid;           // EPI_GRAMW: [batch] sum of squares of (acc - I)
+  float coef_i, coef_g;    // EPI_GRAMW
+  int np_out;              // EPI_GRAMW / EPI_XOUT: bf16 planes written (1..3); plane p holds the p-th split term
+  int64_t plane_out;       //   element offset between output planes
+  bf16_bits* Pn;           // EPI_GRAMW: W planes; EPI_XOUT: X' planes, natural [m][n] (may be null)
+  bf16_bits* Pt;           // EPI_XOUT: X' planes, transposed [n][m] (may be null)
+  float* C32;              // EPI_XOUT: X' in fp32 [m][n] (may be null)
+  const float* Xadd;       // EPI_XOUT: fp32 [m][n] added to acc before writing (may be null)
 };
 
 // Enqueue the GEMM on `stream`.  Returns hipSuccess or the launch error.

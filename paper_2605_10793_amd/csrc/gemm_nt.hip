@@ -326,8 +326,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           *p = g.accumulate ? (*p + acc[i][j][e]) : acc[i][j][e];
         }
       }
-  } else {  // EPI_GRAM
-    float* C = reinterpret_cast<float*>(g.C) + (int64_t)bz * g.batchC;
+  } else if constexpr (EPI == EPI_GRAMW) {
+    const int64_t boff = (int64_t)bz * g.batchC;
     double rsum = 0.0;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -343,12 +343,55 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           const float eye = (m == n) ? 1.0f : 0.0f;
           const float r = acc[i][j][e] - eye;
           part += r * r;
-          C[(int64_t)m * g.ldc + n] = g.coef_i * eye + g.coef_g * acc[i][j][e];
+          float w = g.coef_i * eye + g.coef_g * acc[i][j][e];
+          const int64_t off = boff + (int64_t)m * g.ldc + n;
+          for (int p = 0; p < g.np_out; ++p) {
+            const bf16_bits hb = f32_to_bf16(w);
+            g.Pn[p * g.plane_out + off] = hb;
+            w -= bf16_to_f32(hb);
+          }
         }
         rsum += (double)part;
       }
     rsum = wave_sum_d(rsum);
     if (lane == 0) atomicAdd(g.resid + bz, rsum);
+  } else {  // EPI_XOUT
+    const int64_t boff = (int64_t)bz * g.batchC;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = nw + j * 32 + col;
+        if (n >= g.N) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int mb = mw + i * 32 + 8 * q + 4 * half;   // 4 consecutive rows mb .. mb+3 (M is a multiple of 4)
+          if (mb >= g.M) continue;
+          float v[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            v[r] = acc[i][j][4 * q + r];
+            const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
+            if (g.Xadd) v[r] += g.Xadd[off];
+            if (g.C32) g.C32[off] = v[r];
+          }
+          for (int p = 0; p < g.np_out; ++p) {
+            bf16_bits hb[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              hb[r] = f32_to_bf16(v[r]);
+              v[r] -= bf16_to_f32(hb[r]);
+              if (g.Pn) g.Pn[p * g.plane_out + boff + (int64_t)(mb + r) * g.ldc + n] = hb[r];
+            }
+            if (g.Pt) {
+              uint2 t;
+              t.x = hb[0] | ((uint32_t)hb[1] << 16);
+              t.y = hb[2] | ((uint32_t)hb[3] << 16);
+              *reinterpret_cast<uint2*>(g.Pt + p * g.plane_out + boff + (int64_t)n * g.ldc + mb) = t;
+            }
+          }
+        }
+      }
   }
 }
 
@@ -409,7 +452,8 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
     case EPI_ACT: return launch_epi<EPI_ACT>(a, batch, stream);
     case EPI_F32: return a.ab_f16 ? launch_epi<EPI_F32, true>(a, batch, stream) : launch_epi<EPI_F32>(a, batch, stream);
-    case EPI_GRAM: return launch_epi<EPI_GRAM>(a, batch, stream);
+    case EPI_GRAMW: return launch_epi<EPI_GRAMW>(a, batch, stream);
+    case EPI_XOUT: return launch_epi<EPI_XOUT>(a, batch, stream);
   }
   return hipErrorInvalidValue;
 }

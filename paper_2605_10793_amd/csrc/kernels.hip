@@ -221,23 +221,26 @@ __global__ void __launch_bounds__(256) k_reduce_stats(const float* __restrict__ 
                                                       double* __restrict__ L, unsigned long long* __restrict__ rows,
                                                       unsigned long long* __restrict__ skipped) {
   __shared__ double sh[4];
-  const int h = blockIdx.x;
-  double acc = 0.0, cnt = 0.0;
-  for (int64_t i = threadIdx.x; i < T; i += 256) {
+  const int h = blockIdx.y;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  double acc = 0.0, cnt = 0.0, tot = 0.0;
+  if (i < T) {
+    tot = 1.0;
     const float n = nrm[(int64_t)h * ldn + i];
     if (n > 0.0f) {
       double s = 0.0;
       for (int q = 0; q < slabs; ++q) s += (double)Lpart[((int64_t)h * slabs + q) * ldl + i];
-      acc += s / (double)n;
-      cnt += 1.0;
+      acc = s / (double)n;
+      cnt = 1.0;
     }
   }
   acc = block_sum_d(acc, sh);
   cnt = block_sum_d(cnt, sh);
+  tot = block_sum_d(tot, sh);
   if (threadIdx.x == 0) {
-    L[h] += acc;
-    rows[h] += (unsigned long long)cnt;
-    skipped[h] += (unsigned long long)((double)T - cnt);
+    atomicAdd(L + h, acc);
+    atomicAdd(rows + h, (unsigned long long)cnt);
+    atomicAdd(skipped + h, (unsigned long long)(tot - cnt));
   }
 }
 
@@ -441,7 +444,8 @@ hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, 
 
 hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
                                int heads, double* L, unsigned long long* rows, unsigned long long* skipped, hipStream_t s) {
-  hipLaunchKernelGGL(k_reduce_stats, dim3(heads), dim3(256), 0, s, Lpart, slabs, ldl, nrm, ldn, T, L, rows, skipped);
+  hipLaunchKernelGGL(k_reduce_stats, dim3((unsigned)((T + 255) / 256), heads), dim3(256), 0, s, Lpart, slabs, ldl, nrm, ldn, T, L, rows,
+                     skipped);
   return hipGetLastError();
 }
 
