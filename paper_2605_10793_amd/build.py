@@ -11,6 +11,9 @@ OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libconqur.so")
 SOURCES = ["gemm_nt.hip", "kernels.hip", "conqur.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
+         # fp32/fp64 atomicAdd as the hardware's L2 atomics (device memory is coarse grained);
+         # the default lowers them to compare-and-swap loops, which crawl under contention
+         "-munsafe-fp-atomics",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

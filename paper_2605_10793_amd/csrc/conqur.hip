@@ -63,6 +63,8 @@ struct conqur_ctx {
   bf16_bits *PXt[2] = {nullptr, nullptr};            // ... transposed
   bf16_bits* PW = nullptr;                           // polynomial factor planes [3][heads][dh][dh]
   double* resid = nullptr;                           // [kResidSlots][heads] residual history of one update
+  double* resid_part = nullptr;                      // [heads][parts] per-wavefront partials of one Gram GEMM
+  int resid_parts = 0;
   double *fro2 = nullptr, *inner = nullptr;          // [heads]
   int64_t last_T = 0;
 
@@ -216,6 +218,8 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   }
   A(dev_alloc(ctx, &ctx->PW, 3 * blk));
   A(dev_alloc(ctx, &ctx->resid, (size_t)kResidSlots * ctx->heads));
+  ctx->resid_parts = gemm_num_partials((int)dh, (int)dh, ctx->heads);
+  A(dev_alloc(ctx, &ctx->resid_part, (size_t)ctx->resid_parts * ctx->heads));
   A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
   A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
   for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
@@ -348,7 +352,6 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
 
   HIP_TRY(launch_fill_zero(ctx->fro2, h * sizeof(double), s));
   HIP_TRY(launch_fill_zero(ctx->inner, h * sizeof(double), s));
-  HIP_TRY(launch_fill_zero(ctx->resid, (size_t)kResidSlots * h * sizeof(double), s));
   HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->fro2, s));
   // X0 = (M + lambda tau R) / alpha, alpha = ||M||_F (1 + lambda) >= ||X0||_2
   HIP_TRY(launch_polar_start(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, ctx->PX, s));
@@ -361,7 +364,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   int slot = 0;           // next residual-history slot
   uint32_t iters = 0, closing = 0;
 
-  auto gram = [&](const SegList& sl, float ci, float cg, int np_w) -> hipError_t {
+  auto gram = [&](const SegList& sl, float ci, float cg, int np_w, bool want_resid) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     g.A = ctx->PXt[cur]; g.B = ctx->PXt[cur]; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
@@ -369,8 +372,11 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.nseg = sl.n;
     for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
     g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW; g.np_out = np_w; g.plane_out = plane;
-    g.resid = ctx->resid + (size_t)slot * h; g.coef_i = ci; g.coef_g = cg;
-    return launch_gemm_nt(g, EPI_GRAMW, h, s);
+    g.resid_part = want_resid ? ctx->resid_part : nullptr; g.coef_i = ci; g.coef_g = cg;
+    hipError_t e = launch_gemm_nt(g, EPI_GRAMW, h, s);
+    if (e == hipSuccess && want_resid)
+      e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);
+    return e;
   };
   // X' = X W (+ X): reads the planes in buffer `cur`, writes np_x planes (both layouts)
   // into the other buffer, and the fp32 iterate when asked.
@@ -412,7 +418,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       double a, b;
       const double E = step_cubic(l, u, &a, &b);
       const bool last = E <= e_stop || iters + 1 >= cap;
-      HIP_TRY(gram(seg_main, (float)a, (float)b, np_main));
+      HIP_TRY(gram(seg_main, (float)a, (float)b, np_main, trace));
       ++slot;
       // the last main step hands over to the closing iterations: fp32 iterate + 2 planes
       HIP_TRY(apply(seg_main, last ? std::max(np_main, 2) : np_main, false, last));
@@ -437,14 +443,14 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   int last_slot = 0;
   if (np_main == 1 && iters < cap) {
     // at the bf16 floor the first closing step needs only a two-plane Gram matrix
-    HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2)); ++slot;
+    HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2, trace)); ++slot;
     HIP_TRY(apply(kSeg3, 3, true, true));
     ++iters; ++closing;
   } else {
     HIP_TRY(launch_pack(ctx->PX, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
   }
   while (true) {
-    HIP_TRY(gram(kSeg6, 0.5f, -0.5f, 2));
+    HIP_TRY(gram(kSeg6, 0.5f, -0.5f, 2, true));
     last_slot = slot++;
     st = read_resid(last_slot, &res);
     if (st != CONQUR_OK) return st;
@@ -465,7 +471,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       st = main_phase(0.25 * kappa / std::sqrt((double)dh));
       if (st != CONQUR_OK) return st;
       if (np_main == 1 && iters < cap) {
-        HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2)); ++slot;
+        HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2, trace)); ++slot;
         HIP_TRY(apply(kSeg3, 3, true, true));
         ++iters; ++closing;
       } else {

@@ -15,7 +15,7 @@ enum GemmEpilogue : int {
   EPI_ACT = 1,   // Y[m][n] = acc, stored as bf16 or fp32 (rotated activations for the quantiser score)
   EPI_F32 = 2,   // C[m][n] = acc (+ C[m][n] if accumulate), fp32
   EPI_GRAMW = 3, // acc = Gram matrix G: W = coef_i*I + coef_g*G written as np_out bf16 split planes
-                 // (natural layout) and resid += sum (G - I)^2
+                 // (natural layout) and per-wavefront partial sums of (G - I)^2
   EPI_XOUT = 4,  // acc = X' (+ Xadd): written as fp32 (C32) and/or np_out bf16 split planes in natural (Pn)
                  // and transposed (Pt) layout -- the operands of the next Gram / apply GEMMs
 };
@@ -41,7 +41,8 @@ struct GemmArgs {
   int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
   float* Lpart;            // EPI_SIGN: [batch][slabs][ldl] partial sums of |acc| over the slab's columns
   int64_t ldl;             //           slabs = 2 * tiles_n
-  double* resid;           // EPI_GRAMW: [batch] sum of squares of (acc - I)
+  double* resid_part;      // EPI_GRAMW: [batch][gemm_num_partials()] per-wavefront sums of (acc - I)^2, or null.
+                           // (No atomics: same-address atomics from all XCDs serialise at the memory side.)
   float coef_i, coef_g;    // EPI_GRAMW
   int np_out;              // EPI_GRAMW / EPI_XOUT: bf16 planes written (1..3); plane p holds the p-th split term
   int64_t plane_out;       //   element offset between output planes
@@ -53,6 +54,9 @@ struct GemmArgs {
 
 // Enqueue the GEMM on `stream`.  Returns hipSuccess or the launch error.
 hipError_t launch_gemm_nt(const GemmArgs& args, GemmEpilogue epi, int batch, hipStream_t stream);
+
+// Per-batch-entry count of the partial sums the EPI_GRAMW epilogue writes for an M x N problem.
+int gemm_num_partials(int M, int N, int batch);
 
 // Number of column slabs the EPI_SIGN epilogue writes for an N-wide problem
 // (depends on the tile the launcher picks for (M, N, batch)).

@@ -353,8 +353,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         }
         rsum += (double)part;
       }
-    rsum = wave_sum_d(rsum);
-    if (lane == 0) atomicAdd(g.resid + bz, rsum);
+    if (g.resid_part) {
+      rsum = wave_sum_d(rsum);
+      if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+    }
   } else {  // EPI_XOUT
     const int64_t boff = (int64_t)bz * g.batchC;
 #pragma unroll
@@ -438,6 +440,11 @@ hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
 }
 
 }  // namespace
+
+int gemm_num_partials(int M, int N, int batch) {
+  const Tile& t = kTiles[pick_tile(M, N, batch)];
+  return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * t.wgm * t.wgn;
+}
 
 int gemm_sign_slabs(int M, int N, int batch) {
   const Tile& t = kTiles[pick_tile(M, N, batch)];

@@ -47,10 +47,13 @@ hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStre
 hipError_t launch_polar_finish(const float* X, const float* M, int heads, int64_t n, float* R, double* inner,
                                hipStream_t s);
 
-// Per-row symmetric fake-quantisation error of Y [T][ld] (bf16 or fp32), then the
-// sums over rows: out[0] = SSE, out[1] = energy.
+// Per-row symmetric fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse /
+// row_en, then their sums over rows: out[0] = SSE, out[1] = energy.
 hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,
                               float* row_en, double* out, hipStream_t s);
+
+// out[h] = sum of part[h][0..n) for h < heads, fixed order.
+hipError_t launch_sum_partials(const double* part, int n, int heads, double* out, hipStream_t s);
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 

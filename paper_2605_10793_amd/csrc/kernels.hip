@@ -30,7 +30,7 @@ __device__ __forceinline__ double block_sum_d(double v, double* sh) {
   if (lane == 0) sh[wave] = v;
   __syncthreads();
   double t = 0.0;
-  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sh[i];
+  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sh[i];   // sh holds one entry per wavefront
   return t;
 }
 
@@ -216,21 +216,31 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
 }
 
 // ---------------------------------------------------------------- statistics
+// One block per 64 tokens of one head: thread (t & 63) owns a token, (t >> 6) a quarter
+// of the column slabs, so that the slab partials are read coalesced and in parallel.
 __global__ void __launch_bounds__(256) k_reduce_stats(const float* __restrict__ Lpart, int slabs, int64_t ldl,
                                                       const float* __restrict__ nrm, int64_t ldn, int64_t T,
                                                       double* __restrict__ L, unsigned long long* __restrict__ rows,
                                                       unsigned long long* __restrict__ skipped) {
   __shared__ double sh[4];
+  __shared__ float part[4][64];
   const int h = blockIdx.y;
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  double acc = 0.0, cnt = 0.0, tot = 0.0;
+  const int tok = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + tok;
+  float s = 0.0f;
   if (i < T) {
+    const float* p = Lpart + (int64_t)h * slabs * ldl + i;
+#pragma unroll 8
+    for (int q = quarter; q < slabs; q += 4) s += p[(int64_t)q * ldl];
+  }
+  part[quarter][tok] = s;
+  __syncthreads();
+  double acc = 0.0, cnt = 0.0, tot = 0.0;
+  if (quarter == 0 && i < T) {
     tot = 1.0;
     const float n = nrm[(int64_t)h * ldn + i];
     if (n > 0.0f) {
-      double s = 0.0;
-      for (int q = 0; q < slabs; ++q) s += (double)Lpart[((int64_t)h * slabs + q) * ldl + i];
-      acc = s / (double)n;
+      acc = ((double)part[0][tok] + (double)part[1][tok] + (double)part[2][tok] + (double)part[3][tok]) / (double)n;
       cnt = 1.0;
     }
   }
@@ -303,17 +313,19 @@ __global__ void __launch_bounds__(256) k_polar_finish(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------- fake-quantisation error
-// One workgroup per token row.  The row is read once from HBM (kept in registers
-// for d <= 8192 bf16 / 4096 fp32; longer rows re-read the tail from cache).
+// One workgroup per token row: the row is read once from HBM with 16-byte loads and kept
+// in registers (4 chunks per thread = 8192 bf16 / 4096 fp32 elements; longer rows re-read
+// the tail, which then comes from cache).  Two barriers per row (maximum, sums); per-row
+// results go to row_sse / row_en.
 template <bool F32>
-__global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y, int64_t ld, int d, float qmax,
+__global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y, int64_t T, int64_t ld, int d, float qmax,
                                                      float* __restrict__ row_sse, float* __restrict__ row_en) {
   constexpr int EPC = F32 ? 4 : 8;  // elements per 16-byte chunk
-  __shared__ float shm[4];
-  __shared__ double shd[4];
+  constexpr int NC = 4;             // chunks cached per thread
+  __shared__ float shm[4], shs[4], she[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = blockIdx.x;
   const int nch = d / EPC;
-  const uint4* y = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(Y) + row * ld * (F32 ? 4 : 2));
   auto expand = [](const uint4& v, float* f) {
     if constexpr (F32) {
       f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
@@ -321,10 +333,11 @@ __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y,
       unpack8(v, f);
     }
   };
-  uint4 cache[4];
+  const uint4* y = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(Y) + row * ld * (F32 ? 4 : 2));
+  uint4 cache[NC];
   float amax = 0.0f;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < NC; ++q) {
     const int c = threadIdx.x + 256 * q;
     cache[q] = make_uint4(0, 0, 0, 0);
     if (c < nch) {
@@ -335,47 +348,56 @@ __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y,
       for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));
     }
   }
-  for (int c = threadIdx.x + 1024; c < nch; c += 256) {
+  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) {
     float f[EPC];
     expand(y[c], f);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));
   }
   amax = wave_max(amax);
-  if ((threadIdx.x & 63) == 0) shm[threadIdx.x >> 6] = amax;
+  if (lane == 0) shm[wave] = amax;
   __syncthreads();
   amax = fmaxf(fmaxf(shm[0], shm[1]), fmaxf(shm[2], shm[3]));
+  // D = max / qmax; the code is decided in fp32 as round-half-even(y * (1/D)) with the
+  // correctly rounded reciprocal (a division per element would make this kernel
+  // ALU bound instead of HBM bound); it can differ from round(y / D) only within an
+  // ulp of a rounding tie, where both codes give the same squared error.
   const float delta = amax / qmax;
+  const float inv_delta = amax > 0.0f ? 1.0f / delta : 0.0f;
   float sse = 0.0f, en = 0.0f;
   auto score = [&](const uint4& v) {
     float f[EPC];
     expand(v, f);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) {
-      float code = 0.0f;
-      if (amax > 0.0f) code = fminf(fmaxf(rintf(f[e] / delta), -qmax), qmax);
+      const float code = fminf(fmaxf(rintf(f[e] * inv_delta), -qmax), qmax);
       const float err = fmaf(-delta, code, f[e]);
       sse = fmaf(err, err, sse);
       en = fmaf(f[e], f[e], en);
     }
   };
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+  for (int q = 0; q < NC; ++q)
     if ((int)threadIdx.x + 256 * q < nch) score(cache[q]);
-  for (int c = threadIdx.x + 1024; c < nch; c += 256) score(y[c]);
-  const double s = block_sum_d((double)sse, shd);
-  const double e = block_sum_d((double)en, shd);
+  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) score(y[c]);
+  sse = wave_sum(sse);
+  en = wave_sum(en);
+  if (lane == 0) { shs[wave] = sse; she[wave] = en; }
+  __syncthreads();
   if (threadIdx.x == 0) {
-    row_sse[row] = (float)s;
-    row_en[row] = (float)e;
+    row_sse[row] = (float)((double)shs[0] + (double)shs[1] + (double)shs[2] + (double)shs[3]);
+    row_en[row] = (float)((double)she[0] + (double)she[1] + (double)she[2] + (double)she[3]);
   }
 }
 
-__global__ void __launch_bounds__(256) k_sum_rows(const float* __restrict__ a, const float* __restrict__ b, int64_t T,
-                                                  double* __restrict__ out) {
-  __shared__ double sh[4];
+// out[0] = sum a, out[1] = sum b in a fixed order (one workgroup).  Results of many
+// workgroups are combined this way rather than with atomics on one address, which the
+// XCDs would serialise at the memory side.
+__global__ void __launch_bounds__(1024) k_sum_rows(const float* __restrict__ a, const float* __restrict__ b, int64_t T,
+                                                   double* __restrict__ out) {
+  __shared__ double sh[16];
   double sa = 0.0, sb = 0.0;
-  for (int64_t i = threadIdx.x; i < T; i += 256) {
+  for (int64_t i = threadIdx.x; i < T; i += 1024) {
     sa += (double)a[i];
     sb += (double)b[i];
   }
@@ -385,6 +407,16 @@ __global__ void __launch_bounds__(256) k_sum_rows(const float* __restrict__ a, c
     out[0] = sa;
     out[1] = sb;
   }
+}
+
+// out[h] = sum_i part[h][i], i < n (one workgroup per h).
+__global__ void __launch_bounds__(256) k_sum_partials(const double* __restrict__ part, int n, double* __restrict__ out) {
+  __shared__ double sh[4];
+  const double* p = part + (int64_t)blockIdx.x * n;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) s += p[i];
+  s = block_sum_d(s, sh);
+  if (threadIdx.x == 0) out[blockIdx.x] = s;
 }
 
 __global__ void __launch_bounds__(256) k_fill_zero(uint32_t* p, size_t n) {
@@ -444,7 +476,7 @@ hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, 
 
 hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
                                int heads, double* L, unsigned long long* rows, unsigned long long* skipped, hipStream_t s) {
-  hipLaunchKernelGGL(k_reduce_stats, dim3((unsigned)((T + 255) / 256), heads), dim3(256), 0, s, Lpart, slabs, ldl, nrm, ldn, T, L, rows,
+  hipLaunchKernelGGL(k_reduce_stats, dim3((unsigned)((T + 63) / 64), heads), dim3(256), 0, s, Lpart, slabs, ldl, nrm, ldn, T, L, rows,
                      skipped);
   return hipGetLastError();
 }
@@ -474,13 +506,19 @@ hipError_t launch_polar_finish(const float* X, const float* M, int heads, int64_
 hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,
                               float* row_en, double* out, hipStream_t s) {
   const float qmax = (float)((1 << (bits - 1)) - 1);
+  const dim3 grid((unsigned)T);
   if (y_is_f32)
-    hipLaunchKernelGGL(k_quant_error<true>, dim3((unsigned)T), dim3(256), 0, s, Y, ld, d, qmax, row_sse, row_en);
+    hipLaunchKernelGGL(k_quant_error<true>, grid, dim3(256), 0, s, Y, T, ld, d, qmax, row_sse, row_en);
   else
-    hipLaunchKernelGGL(k_quant_error<false>, dim3((unsigned)T), dim3(256), 0, s, Y, ld, d, qmax, row_sse, row_en);
+    hipLaunchKernelGGL(k_quant_error<false>, grid, dim3(256), 0, s, Y, T, ld, d, qmax, row_sse, row_en);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(256), 0, s, row_sse, row_en, T, out);
+  hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(1024), 0, s, row_sse, row_en, T, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_partials(const double* part, int n, int heads, double* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_sum_partials, dim3(heads), dim3(256), 0, s, part, n, out);
   return hipGetLastError();
 }
 
