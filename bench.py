@@ -25,6 +25,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16/fp16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per step_batch GEMM launch pair on c3, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes scaled by a
+# 256 MiB copy (profiles/bench_c3_pmc_traffic_mfma.txt): fetch 224.5 MiB + write 81.3 MiB.
+MEASURED_TRAFFIC_BYTES = {"c3": 3.21e8}
 
 
 def cpu_baseline(w, X0, R0, sample_tokens):
@@ -59,6 +62,9 @@ def main():
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also run three 256 MiB device-to-device copies (the known-size kernel that scales "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the path is single-device; see DESIGN.md for how it would "
@@ -90,6 +96,12 @@ def main():
         _, st = cal.update_rotation()
         return sse / en, st
 
+    if args.pmc_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     for i in range(W):
         one_step(i)
     torch.cuda.synchronize()
@@ -133,7 +145,8 @@ def main():
         "roofline": {
             "bound": "mfma", "kernel": "gemm_nt_kernel (rotate+corner launch and accumulate launch of step_batch)",
             "achieved": step_flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": step_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
+            "frac": step_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
             "flops_per_launch_pair": step_flops, "ms_per_launch_pair": gemm_ms,
         },
         "roofline_polar": {
