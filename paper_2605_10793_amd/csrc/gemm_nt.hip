@@ -7,11 +7,11 @@
 // load-issue latencies.
 //
 // Operand path: HBM/L2 -> LDS directly (buffer_load ... lds, 16 bytes per lane, no
-// register staging), 4 LDS stages of 32 K-elements, fragments double buffered in
+// register staging), 2 LDS stages of 64 K-elements, fragments double buffered in
 // registers, one fence-free barrier per K step placed between MFMA groups.
 //
-// LDS layout: a tile row is 32 bf16 = 64 bytes = 4 chunks of 16 bytes; chunk c of row r
-// sits at physical chunk c ^ ((r >> 2) & 3), which spreads any 16 consecutive rows of
+// LDS layout: a tile row is 64 bf16 = 128 bytes = 8 chunks of 16 bytes; chunk c of row r
+// sits at physical chunk c ^ ((r >> 1) & 7), which spreads any 16 consecutive rows of
 // one logical chunk (what a ds_read_b128 quarter-wave touches) over all 64 banks;
 // measured SQ_LDS_BANK_CONFLICT = 0.
 #include "gemm_nt.h"
@@ -20,11 +20,11 @@ namespace conqur {
 
 namespace {
 
-constexpr int BK = 32;      // K elements per pipeline stage (one LDS tile row = 64 bytes = 4 chunks of 16 bytes)
-constexpr int NSTAGE = 4;   // LDS stages: three tiles in flight behind the one being consumed
+constexpr int BK = 64;      // K elements per pipeline stage (one LDS tile row = 128 bytes = 8 chunks of 16 bytes)
+constexpr int NSTAGE = 2;   // LDS stages (2 x 64 KiB for the 256 x 256 tile); measured faster than 4 stages of 32
 
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4);
+  return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = simm16[15:14]:[3:0], expcnt and lgkmcnt left at max).
@@ -50,10 +50,10 @@ template <int BM, int BN, int WGM, int WGN, int EPI, bool F16>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs g, const int tiles_m, const int tiles_n) {
   constexpr int NW = WGM * WGN;                 // wavefronts per workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
-  constexpr int NLA = BM / 16, NLB = BN / 16;   // wave-wide 1 KiB loads per stage (16 tile rows each)
+  constexpr int NLA = BM / 8, NLB = BN / 8;     // wave-wide 1 KiB loads per stage (8 tile rows each)
   constexpr int QA = NLA / NW, QB = NLB / NW;   // ... per wavefront
   static_assert(NLA % NW == 0 && NLB % NW == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
-  constexpr int STAGE = (BM + BN) * 64;
+  constexpr int STAGE = (BM + BN) * 128;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -85,22 +85,22 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   const bf16_bits* Bb = g.B + (int64_t)bz * g.batchB;
 
   // Global -> LDS without passing through registers: each buffer_load ... lds moves
-  // 64 lanes x 16 bytes = 16 tile rows into 1 KiB of LDS (lane L lands at L*16).
-  // Lane L therefore fetches the chunk that the swizzled layout stores at row L/4,
-  // physical chunk L%4.  Rows past M (N) lie past the descriptor's range and read 0.
-  const int lrow = lane >> 2, lpc = lane & 3;
+  // 64 lanes x 16 bytes = 8 tile rows into 1 KiB of LDS (lane L lands at L*16).
+  // Lane L therefore fetches the chunk that the swizzled layout stores at row L/8,
+  // physical chunk L%8.  Rows past M (N) lie past the descriptor's range and read 0.
+  const int lrow = lane >> 3, lpc = lane & 7;
   uint32_t offA[QA], offB[QB];
   int chunkA[QA], chunkB[QB];
 #pragma unroll
   for (int q = 0; q < QA; ++q) {
-    const int row = (q * NW + wave) * 16 + lrow;
-    chunkA[q] = lpc ^ ((row >> 2) & 3);
+    const int row = (q * NW + wave) * 8 + lrow;
+    chunkA[q] = lpc ^ ((row >> 1) & 7);
     offA[q] = (m0 + row < g.M) ? (uint32_t)(((int64_t)(m0 + row) * g.lda + chunkA[q] * 8) * 2) : kOobOffset;
   }
 #pragma unroll
   for (int q = 0; q < QB; ++q) {
-    const int row = (q * NW + wave) * 16 + lrow;
-    chunkB[q] = lpc ^ ((row >> 2) & 3);
+    const int row = (q * NW + wave) * 8 + lrow;
+    chunkB[q] = lpc ^ ((row >> 1) & 7);
     offB[q] = (n0 + row < g.N) ? (uint32_t)(((int64_t)(n0 + row) * g.ldb + chunkB[q] * 8) * 2) : kOobOffset;
   }
   const uint32_t recA = (uint32_t)((((int64_t)g.M - 1) * g.lda + BK) * 2);
@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
     } else {
       const int qb = q - QA;
       const uint32_t off = tail ? offBt[qb] : offB[qb];
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sa + BM * 64 + (qb * NW + wave) * 1024),
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (__attribute__((address_space(3))) void*)(sa + BM * 128 + (qb * NW + wave) * 1024),
                                                16, off, 0, 0, 0);
     }
   };
@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
 
   auto read_frag = [&](int buf, int r, const unsigned char* sa, int kk) {
     // read number r of a substep, in the order the MFMAs need them: a0, b0..b(TN-1), a1..a(TM-1)
-    const unsigned char* sb = sa + BM * 64;
+    const unsigned char* sb = sa + BM * 128;
     if (r == 0) fa[buf][0] = *reinterpret_cast<const bf16x8*>(sa + lds_off(wm * WM + col, kk * 2 + half));
     else if (r <= TN) fb[buf][r - 1] = *reinterpret_cast<const bf16x8*>(sb + lds_off(wn * WN + (r - 1) * 32 + col, kk * 2 + half));
     else fa[buf][r - TN] = *reinterpret_cast<const bf16x8*>(sa + lds_off(wm * WM + (r - TN) * 32 + col, kk * 2 + half));
