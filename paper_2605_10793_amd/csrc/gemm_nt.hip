@@ -398,8 +398,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
 }
 
 struct Tile { int bm, bn, wgm, wgn; float eff; };
-constexpr Tile kTiles[] = {{256, 256, 2, 4, 1.0f}, {256, 128, 4, 2, 0.85f}, {128, 128, 2, 2, 0.7f}, {64, 64, 2, 2, 0.35f}};
-constexpr int kNumTiles = 4;
+constexpr Tile kTiles[] = {{256, 256, 2, 4, 1.0f}, {256, 128, 4, 2, 0.85f}, {128, 128, 2, 2, 0.7f}, {64, 64, 2, 2, 0.35f},
+                           {192, 192, 3, 2, 0.9f}};   // 192: fills the chip exactly at d = 3072
+constexpr int kNumTiles = 5;
 
 int pick_tile(int M, int N, int batch) {
   int best = 0;
@@ -435,6 +436,7 @@ hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
     case 0: return launch_one<256, 256, 2, 4, EPI, F16>(a, batch, stream);
     case 1: return launch_one<256, 128, 4, 2, EPI, F16>(a, batch, stream);
     case 2: return launch_one<128, 128, 2, 2, EPI, F16>(a, batch, stream);
+    case 4: return launch_one<192, 192, 3, 2, EPI, F16>(a, batch, stream);
     default: return launch_one<64, 64, 2, 2, EPI, F16>(a, batch, stream);
   }
 }
