@@ -61,7 +61,7 @@ struct conqur_ctx {
   float* PX = nullptr;                               // polar iterate, fp32 [heads][dh][dh]
   bf16_bits *PXn[2] = {nullptr, nullptr};            // iterate as bf16 split planes [3][heads][dh][dh], ping-pong
   bf16_bits *PXt[2] = {nullptr, nullptr};            // ... transposed
-  bf16_bits* PW = nullptr;                           // polynomial factor planes [3][heads][dh][dh]
+  bf16_bits *PW = nullptr, *PW2 = nullptr;           // polynomial factor planes [3][heads][dh][dh]
   double* resid = nullptr;                           // [kResidSlots][heads] residual history of one update
   double* resid_part = nullptr;                      // [heads][parts] per-wavefront partials of one Gram GEMM
   int resid_parts = 0;
@@ -217,6 +217,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
     A(dev_alloc(ctx, &ctx->PXt[b], 3 * blk));
   }
   A(dev_alloc(ctx, &ctx->PW, 3 * blk));
+  A(dev_alloc(ctx, &ctx->PW2, 3 * blk));
   A(dev_alloc(ctx, &ctx->resid, (size_t)kResidSlots * ctx->heads));
   ctx->resid_parts = gemm_num_partials((int)dh, (int)dh, ctx->heads);
   A(dev_alloc(ctx, &ctx->resid_part, (size_t)ctx->resid_parts * ctx->heads));
@@ -380,20 +381,31 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   };
   // X' = X W (+ X): reads the planes in buffer `cur`, writes np_x planes (both layouts)
   // into the other buffer, and the fp32 iterate when asked.
-  auto apply = [&](const SegList& sl, int np_x, bool add_x, bool write_f32) -> hipError_t {
+  auto apply = [&](const SegList& sl, const bf16_bits* W, int np_t, int np_n, bool add_x, bool write_f32) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
-    g.A = ctx->PXn[cur]; g.B = ctx->PW; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.A = ctx->PXn[cur]; g.B = W; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
     g.M = g.N = g.K = dh;
     g.nseg = sl.n;
     for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
-    g.ldc = dh; g.batchC = blk; g.np_out = np_x; g.plane_out = plane;
+    g.ldc = dh; g.batchC = blk; g.np_out = np_t; g.np_out_n = np_n; g.plane_out = plane;
     g.Pn = ctx->PXn[cur ^ 1]; g.Pt = ctx->PXt[cur ^ 1];
     g.Xadd = add_x ? ctx->PX : nullptr;
     g.C32 = write_f32 ? ctx->PX : nullptr;
     hipError_t e = launch_gemm_nt(g, EPI_XOUT, h, s);
     cur ^= 1;
     return e;
+  };
+  // W2 = D + 1.5 D^2 from the planes of D = (I - G)/2 in PW (D is symmetric, so D D^T = D^2)
+  auto square_correction = [&]() -> hipError_t {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ctx->PW; g.B = ctx->PW; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.M = g.N = g.K = dh;
+    g.nseg = 1;   // D^2 is second order small: single bf16 planes are ample
+    g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW2; g.np_out = 2; g.plane_out = plane;
+    g.Padd = ctx->PW; g.np_add = 2; g.coef_i = 0.0f; g.coef_g = 1.5f;
+    return launch_gemm_nt(g, EPI_GRAMW, h, s);
   };
   std::vector<double> hist((size_t)kResidSlots * h);
   auto read_resid = [&](int sl_idx, double* worst) -> conqur_status {
@@ -420,8 +432,9 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       const bool last = E <= e_stop || iters + 1 >= cap;
       HIP_TRY(gram(seg_main, (float)a, (float)b, np_main, trace));
       ++slot;
-      // the last main step hands over to the closing iterations: fp32 iterate + 2 planes
-      HIP_TRY(apply(seg_main, last ? std::max(np_main, 2) : np_main, false, last));
+      // the last main step hands over to the closing iterations: fp32 iterate, 3 transposed planes for
+      // the fp32-equivalent Gram matrix, 2 natural planes for the correction product
+      HIP_TRY(apply(seg_main, ctx->PW, last ? 3 : np_main, last ? 2 : np_main, false, last));
       ++iters;
       if (trace) std::fprintf(stderr, "[conqur] polar main step %d: [l,u]=[%.3e,%.3f] a=%.4f b=%.4f ripple=%.3e planes=%d\n", k, l, u, a, b, E, np_main);
       if (last) break;
@@ -434,21 +447,17 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   conqur_status st = main_phase(0.5 * lam_eff / ((1.0 + lam_eff) * std::sqrt((double)dh)));
   if (st != CONQUR_OK) return st;
 
-  // ---- closing iterations: Newton-Schulz steps X <- X + X (I - X^T X)/2 with the Gram
-  // matrix in fp32-equivalent arithmetic; the correction is small, so two planes per
-  // operand suffice for the product and the fp32 iterate is added in the epilogue.
+  // ---- closing iterations, Gram matrix in fp32-equivalent arithmetic (3 planes, 6 products).
+  // With D = (I - X^T X)/2 the Newton-Schulz steps are X <- X + X D (cubic) and
+  // X <- X + X (D + 1.5 D^2) (quintic, error e -> O(e^3): one step takes the bf16 floor of the
+  // main phase to the fp32 floor).  The correction is small, so two planes per operand
+  // suffice for the product; the fp32 iterate is added in the epilogue.
   bool converged = false;
   int kicks = 0;
   double res = 0.0;
   int last_slot = 0;
-  if (np_main == 1 && iters < cap) {
-    // at the bf16 floor the first closing step needs only a two-plane Gram matrix
-    HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2, trace)); ++slot;
-    HIP_TRY(apply(kSeg3, 3, true, true));
-    ++iters; ++closing;
-  } else {
+  if (iters == 0 || cap <= iters)   // no main step ran (or the cap cut it): planes of the fp32 iterate
     HIP_TRY(launch_pack(ctx->PX, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
-  }
   while (true) {
     HIP_TRY(gram(kSeg6, 0.5f, -0.5f, 2, true));
     last_slot = slot++;
@@ -458,8 +467,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     if (!std::isfinite(res)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
     if (res <= tol) { converged = true; break; }
     if (iters >= cap || slot >= kResidSlots - 8) break;
-    if (res > 0.45 && kicks < 2 && iters + 8 < cap) {
-      // Some singular value is still (near) zero: either far below the assumed bound or
+    if (res > 0.7 && kicks < 2 && iters + 8 < cap) {
+      // Some singular values are still (near) zero: either far below the assumed bound or
       // pinned there by an exact symmetry of M (identical columns, which identical
       // corner-sign columns produce and which the iteration, rounding included,
       // preserves).  Nudge the iterate towards the previous rotation -- on those
@@ -470,16 +479,14 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       ++kicks;
       st = main_phase(0.25 * kappa / std::sqrt((double)dh));
       if (st != CONQUR_OK) return st;
-      if (np_main == 1 && iters < cap) {
-        HIP_TRY(gram(kSeg3, 0.5f, -0.5f, 2, trace)); ++slot;
-        HIP_TRY(apply(kSeg3, 3, true, true));
-        ++iters; ++closing;
-      } else {
-        HIP_TRY(launch_pack(ctx->PX, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
-      }
       continue;
     }
-    HIP_TRY(apply(kSeg3, 3, true, true));
+    const bf16_bits* W = ctx->PW;
+    if (res <= 1e-2 * std::sqrt((double)dh)) {   // rms deviation of the singular values below 1e-2
+      HIP_TRY(square_correction());
+      W = ctx->PW2;
+    }
+    HIP_TRY(apply(kSeg3, W, 3, 2, true, true));
     ++iters; ++closing;
   }
 

@@ -44,7 +44,11 @@ struct GemmArgs {
   double* resid_part;      // EPI_GRAMW: [batch][gemm_num_partials()] per-wavefront sums of (acc - I)^2, or null.
                            // (No atomics: same-address atomics from all XCDs serialise at the memory side.)
   float coef_i, coef_g;    // EPI_GRAMW
-  int np_out;              // EPI_GRAMW / EPI_XOUT: bf16 planes written (1..3); plane p holds the p-th split term
+  int np_out;              // EPI_GRAMW: planes of W written; EPI_XOUT: transposed planes (Pt) written (1..3);
+                           // plane p holds the p-th bf16 split term
+  int np_out_n;            // EPI_XOUT: natural planes (Pn) written (<= 3)
+  const bf16_bits* Padd;   // EPI_GRAMW: np_add planes [m][n] (same pitch / plane offset) whose sum is added to W,
+  int np_add;              //            or null: W = coef_i*I + coef_g*acc + sum_p Padd[p]
   int64_t plane_out;       //   element offset between output planes
   bf16_bits* Pn;           // EPI_GRAMW: W planes; EPI_XOUT: X' planes, natural [m][n] (may be null)
   bf16_bits* Pt;           // EPI_XOUT: X' planes, transposed [n][m] (may be null)

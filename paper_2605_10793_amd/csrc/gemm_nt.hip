@@ -345,6 +345,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           part += r * r;
           float w = g.coef_i * eye + g.coef_g * acc[i][j][e];
           const int64_t off = boff + (int64_t)m * g.ldc + n;
+          for (int p = 0; p < g.np_add; ++p) w += bf16_to_f32(g.Padd[p * g.plane_out + off]);
           for (int p = 0; p < g.np_out; ++p) {
             const bf16_bits hb = f32_to_bf16(w);
             g.Pn[p * g.plane_out + off] = hb;
@@ -377,15 +378,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
             if (g.Xadd) v[r] += g.Xadd[off];
             if (g.C32) g.C32[off] = v[r];
           }
-          for (int p = 0; p < g.np_out; ++p) {
+          const int np_max = g.np_out > g.np_out_n ? g.np_out : g.np_out_n;
+          for (int p = 0; p < np_max; ++p) {
             bf16_bits hb[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               hb[r] = f32_to_bf16(v[r]);
               v[r] -= bf16_to_f32(hb[r]);
-              if (g.Pn) g.Pn[p * g.plane_out + boff + (int64_t)(mb + r) * g.ldc + n] = hb[r];
+              if (p < g.np_out_n) g.Pn[p * g.plane_out + boff + (int64_t)(mb + r) * g.ldc + n] = hb[r];
             }
-            if (g.Pt) {
+            if (p < g.np_out) {
               uint2 t;
               t.x = hb[0] | ((uint32_t)hb[1] << 16);
               t.y = hb[2] | ((uint32_t)hb[3] << 16);
