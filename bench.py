@@ -10,7 +10,10 @@ batch is rank deficient at d = 4096).  Inputs are resident in HBM before the tim
 region.  Prints ONE JSON line.
 
   value            tokens/s of rotate+corner+accumulate alone (the metric's first
-                   half), from HIP events around conqur_step_batch's kernels
+                   half): tokens per batch / device time of conqur_step_batch, from
+                   one HIP event pair around the call's kernels, over the K timed steps
+  stage_ms, roofline  from a second pass over the same K steps with an event pair
+                   around every kernel (per-kernel durations) and in-kernel clock probes
   ms_per_procrustes  the metric's second half: device ms per conqur_update_rotation
   ms_per_step      wall-clock per whole step (step_batch + quant_error + update)
 """
@@ -87,7 +90,7 @@ def main():
     R0 = I.initial_rotation(w)
     dev = [B.to_device(x, w.dtype) for x in host]
     cal = B.Calibrator(d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
-    cal.set_timing(True)
+    cal.set_timing(1)               # one event pair around each whole call
 
     def one_step(i):
         X = dev[i % n_distinct]
@@ -105,22 +108,35 @@ def main():
     for i in range(W):
         one_step(i)
     torch.cuda.synchronize()
-    acc = {k: 0.0 for k in ("prep", "rotate", "accumulate", "stats", "update", "quant_rotate", "quant_error")}
+    whole = {k: 0.0 for k in ("step", "quant", "update")}
     iters = 0
     rel = []
     t0 = time.perf_counter()
     for i in range(W, W + K):
         r, st = one_step(i)
         tm = cal.timing()           # stream is already synchronised by update_rotation
-        for k in acc:
-            acc[k] += tm[k]
+        for k in whole:
+            whole[k] += tm[k]
         iters += st[0]["iters"]
         rel.append(r)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    for k in whole:
+        whole[k] /= K
+    # Second pass over the same K steps with an event pair around every kernel stage and the in-kernel clock
+    # probes: the per-kernel durations the rooflines use.  (The extra event records serialise kernel launches,
+    # so these stages sum to slightly more than the whole-call times of the first pass.)
+    cal.set_timing(2)
+    acc = {k: 0.0 for k in ("prep", "rotate", "accumulate", "stats", "update", "quant_rotate", "quant_error")}
+    for i in range(W, W + K):
+        one_step(i)
+        tm = cal.timing()
+        for k in acc:
+            acc[k] += tm[k]
+    probe = cal.clock_probe()       # of the last step's two GEMM launches
     for k in acc:
         acc[k] /= K
-    step_ms = acc["prep"] + acc["rotate"] + acc["accumulate"] + acc["stats"]
+    step_ms = whole["step"]
     gemm_ms = acc["rotate"] + acc["accumulate"]
     dh = w.dh
     step_flops = 4.0 * T * dh * dh * w.heads            # rotate + accumulate, per batch
@@ -137,10 +153,12 @@ def main():
         "config": {"workload": f"{w.name}: d={d}, heads={w.heads}, {w.dtype} activations, {T} tokens/batch, one "
                                f"Procrustes update per batch, prox_lambda={w.prox_lambda}, fp32 M and R",
                    "tokens_per_batch": T, "d": d, "heads": w.heads},
-        "ms_per_procrustes": acc["update"],
+        "ms_per_procrustes": whole["update"],
+        "ms_per_quant_error": whole["quant"],
         "polar_iters_per_update": iters / K,
         "end_to_end_tokens_per_s": T * K / wall,
         "stage_ms": acc,
+        "stage_ms_note": "second pass of the same steps with an event pair around every kernel stage",
         "int4_rel_err_first_last": [rel[0], rel[-1]],
         "roofline": {
             "bound": "mfma", "kernel": "gemm_nt_kernel (rotate+corner launch and accumulate launch of step_batch)",
@@ -148,6 +166,10 @@ def main():
             "frac": step_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
             "flops_per_launch_pair": step_flops, "ms_per_launch_pair": gemm_ms,
+            "measured_over": "per-kernel HIP events on the library's stream, second pass of the same steps",
+            # in-kernel probe: the shader clock the chip sustains while these kernels' MFMAs run (the published peak
+            # assumes 2400 MHz) and where each launch's time goes
+            "clock_probe": probe,
         },
         "roofline_polar": {
             "bound": "mfma", "achieved": polar_flops / (acc["update"] * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,

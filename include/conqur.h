@@ -148,15 +148,27 @@ conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float
  */
 conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs_host, float* norms_host);
 
-/* Per-stage device times (ms) of the most recent call of each kind, measured with
- * HIP events on the context's stream when timing is enabled (enable != 0 adds two
- * event records per stage).  out_host: HOST, 8 floats:
+/* Device times (ms) of the most recent call of each kind, measured with HIP events on the
+ * context's stream.  level 0: off.  level 1: one event pair around each whole call (what a
+ * caller's pipeline sees: the call's kernels run back to back).  level 2: additionally one
+ * pair per stage -- the records between the kernels keep one kernel's launch from
+ * overlapping the previous kernel's tail, so the stages sum to more than the whole call --
+ * and the clock probes of conqur_get_clock_probe.  out_host: HOST, 12 floats:
  * [0] step: prepare (norms + transposed operand)  [1] step: rotate+corner GEMM
  * [2] step: accumulate GEMM                       [3] step: statistics reduction
  * [4] update: whole polar update                  [5] quant: rotate GEMM
- * [6] quant: error kernel                         [7] reserved                      */
-conqur_status conqur_set_timing(conqur_ctx* ctx, int enable);
+ * [6] quant: error kernel                         [7] whole conqur_step_batch
+ * [8] whole conqur_quant_error (device part)      [9..11] reserved (0)
+ * Entries whose events were not recorded at the current level are 0.                       */
+conqur_status conqur_set_timing(conqur_ctx* ctx, int level);
 conqur_status conqur_get_timing(conqur_ctx* ctx, float* out_host);
+
+/* Clock probe of the two GEMM launches of the most recent conqur_step_batch that ran with timing
+ * level 2: means over the launch's workgroups.  out_host: HOST, 8 floats:
+ * [0] shader clock (MHz) sustained during the rotate+corner GEMM's main loop  [1] its main-loop time (us)
+ * [2] its prologue (first operand tiles arriving) (us)      [3] its epilogue (us)
+ * [4..7] the same for the accumulate GEMM.  Zeros if no probe was taken.  Synchronises.           */
+conqur_status conqur_get_clock_probe(conqur_ctx* ctx, float* out_host);
 
 /* Last error text of this context (HOST string owned by the context; "" if none). */
 const char* conqur_last_error(const conqur_ctx* ctx);

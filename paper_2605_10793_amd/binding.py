@@ -23,7 +23,7 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
     "conqur_quant_error", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
-    "conqur_set_timing", "conqur_get_timing", "conqur_last_error", "conqur_destroy", "conqur_version",
+    "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
 
@@ -80,6 +80,8 @@ def load() -> ctypes.CDLL:
         L.conqur_set_timing.argtypes = [vp, i32]
         L.conqur_get_timing.restype = i32
         L.conqur_get_timing.argtypes = [vp, vp]
+        L.conqur_get_clock_probe.restype = i32
+        L.conqur_get_clock_probe.argtypes = [vp, vp]
         L.conqur_last_error.restype = ctypes.c_char_p
         L.conqur_last_error.argtypes = [vp]
         L.conqur_destroy.restype = None
@@ -183,14 +185,22 @@ class Calibrator:
         self._check(self._lib.conqur_get_last_corners(self._h, _np_ptr(S), _np_ptr(nrm)))
         return S, nrm
 
-    def set_timing(self, enable: bool) -> None:
-        self._check(self._lib.conqur_set_timing(self._h, int(enable)))
+    def set_timing(self, level) -> None:
+        """0 off, 1 (or True) whole-call events, 2 per-stage events and GEMM clock probes as well."""
+        self._check(self._lib.conqur_set_timing(self._h, int(level)))
 
     def timing(self) -> dict:
-        out = np.zeros(8, dtype=np.float32)
+        out = np.zeros(12, dtype=np.float32)
         self._check(self._lib.conqur_get_timing(self._h, _np_ptr(out)))
-        keys = ["prep", "rotate", "accumulate", "stats", "update", "quant_rotate", "quant_error"]
+        keys = ["prep", "rotate", "accumulate", "stats", "update", "quant_rotate", "quant_error", "step", "quant"]
         return {k: float(out[i]) for i, k in enumerate(keys)}
+
+    def clock_probe(self) -> dict:
+        """Sustained shader clock and prologue / main-loop / epilogue split of the last timed step's two GEMMs."""
+        out = np.zeros(8, dtype=np.float32)
+        self._check(self._lib.conqur_get_clock_probe(self._h, _np_ptr(out)))
+        keys = ["clock_mhz", "loop_us", "prologue_us", "epilogue_us"]
+        return {g: {k: float(out[4 * j + i]) for i, k in enumerate(keys)} for j, g in enumerate(("rotate", "accumulate"))}
 
 
 def to_device(x: np.ndarray, dtype: str, device: str = "cuda:0"):

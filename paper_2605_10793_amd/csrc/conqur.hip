@@ -27,8 +27,10 @@ constexpr SegList kSeg6 = {6, {2, 1, 0, 1, 0, 0}, {0, 1, 2, 0, 1, 0}};  // all t
 constexpr SegList kSeg3x1 = {3, {2, 1, 0}, {0, 0, 0}};                   // 3-plane left operand, exact right operand
 
 constexpr int kResidSlots = 512;
+constexpr int kClkMaxWorkgroups = 8192;   // clock probes are taken for GEMM launches of at most this many workgroups
 
-enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_COUNT };
+enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_STEP, ST_QUANT, ST_COUNT };
+constexpr int kTimingSlots = 12;
 
 }  // namespace
 
@@ -68,7 +70,9 @@ struct conqur_ctx {
   double *fro2 = nullptr, *inner = nullptr;          // [heads]
   int64_t last_T = 0;
 
-  bool timing = false;
+  int timing = 0;   // 0 off, 1 whole-call events, 2 per-stage events and GEMM clock probes as well
+  unsigned long long* clk[2] = {nullptr, nullptr};   // clock probes of the step's rotate / accumulate GEMM
+  int clk_wg[2] = {0, 0};                            // workgroups that wrote them in the last step (0: none)
   hipEvent_t ev[ST_COUNT][2]{};
   bool ev_valid[ST_COUNT]{};
   std::vector<void*> allocs;
@@ -100,12 +104,12 @@ hipError_t dev_alloc(conqur_ctx* c, T** p, size_t count) {
 }
 
 struct StageTimer {
-  conqur_ctx* c; int st;
-  StageTimer(conqur_ctx* c_, int st_) : c(c_), st(st_) {
-    if (c->timing) (void)hipEventRecord(c->ev[st][0], c->stream);
+  conqur_ctx* c; int st; bool on;
+  StageTimer(conqur_ctx* c_, int st_, int level = 2) : c(c_), st(st_), on(c_->timing >= level) {
+    if (on) (void)hipEventRecord(c->ev[st][0], c->stream);
   }
   ~StageTimer() {
-    if (c->timing) { (void)hipEventRecord(c->ev[st][1], c->stream); c->ev_valid[st] = true; }
+    if (on) { (void)hipEventRecord(c->ev[st][1], c->stream); c->ev_valid[st] = true; }
   }
 };
 
@@ -223,6 +227,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   A(dev_alloc(ctx, &ctx->resid_part, (size_t)ctx->resid_parts * ctx->heads));
   A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
   A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
+  for (int k = 0; k < 2; ++k) A(dev_alloc(ctx, &ctx->clk[k], (size_t)4 * kClkMaxWorkgroups));
   for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
     for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreate(&ctx->ev[s][k]);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->R, R0_host, blk * sizeof(float), hipMemcpyHostToDevice, ctx->stream);
@@ -239,16 +244,40 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
 
 conqur_status conqur_set_timing(conqur_ctx* ctx, int enable) {
   if (!ctx) return CONQUR_EINVAL;
-  ctx->timing = enable != 0;
+  if (enable < 0 || enable > 2) return fail(ctx, CONQUR_EINVAL, "set_timing: level must be 0, 1 or 2");
+  ctx->timing = enable;
+  for (int s = 0; s < ST_COUNT; ++s) ctx->ev_valid[s] = false;
+  ctx->clk_wg[0] = ctx->clk_wg[1] = 0;
   return CONQUR_OK;
 }
 
 conqur_status conqur_get_timing(conqur_ctx* ctx, float* out) {
   if (!ctx || !out) return CONQUR_EINVAL;
   HIP_TRY(hipStreamSynchronize(ctx->stream));
-  for (int s = 0; s < 8; ++s) out[s] = 0.0f;
+  for (int s = 0; s < kTimingSlots; ++s) out[s] = 0.0f;
   for (int s = 0; s < ST_COUNT; ++s)
     if (ctx->ev_valid[s]) HIP_TRY(hipEventElapsedTime(&out[s], ctx->ev[s][0], ctx->ev[s][1]));
+  return CONQUR_OK;
+}
+
+conqur_status conqur_get_clock_probe(conqur_ctx* ctx, float* out) {
+  if (!ctx || !out) return CONQUR_EINVAL;
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  HIP_TRY(hipStreamSynchronize(ctx->stream));
+  for (int k = 0; k < 2; ++k) {
+    float* o = out + 4 * k;
+    o[0] = o[1] = o[2] = o[3] = 0.0f;
+    const int n = ctx->clk_wg[k];
+    if (n <= 0) continue;
+    std::vector<unsigned long long> h((size_t)4 * n);
+    HIP_TRY(hipMemcpy(h.data(), ctx->clk[k], h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    double cyc = 0, loop = 0, pro = 0, epi = 0;
+    for (int i = 0; i < n; ++i) { cyc += (double)h[4 * i]; loop += (double)h[4 * i + 1]; pro += (double)h[4 * i + 2]; epi += (double)h[4 * i + 3]; }
+    o[0] = loop > 0 ? (float)(100.0 * cyc / loop) : 0.0f;   // ticks are 10 ns
+    o[1] = (float)(loop / n * 0.01);
+    o[2] = (float)(pro / n * 0.01);
+    o[3] = (float)(epi / n * 0.01);
+  }
   return CONQUR_OK;
 }
 
@@ -259,6 +288,7 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
   const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
   const int64_t Tk = round_up(T, 64);
   hipStream_t s = ctx->stream;
+  StageTimer whole(ctx, ST_STEP, 1);   // ends when the function returns
   {
     StageTimer tm(ctx, ST_PREP);
     HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, s));
@@ -278,6 +308,9 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
     slabs = gemm_sign_slabs(g.M, g.N, ctx->heads);
     if (slabs > ctx->slabs_max) return fail(ctx, CONQUR_EHIP, "internal: slab count exceeds workspace");
     g.Lpart = ctx->Lpart; g.ldl = ctx->tmax;
+    const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
+    ctx->clk_wg[0] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
+    g.clk = ctx->clk_wg[0] ? ctx->clk[0] : nullptr;
     HIP_TRY(launch_gemm_nt(g, EPI_SIGN, ctx->heads, s));
   }
   {
@@ -293,6 +326,9 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
     g.C = ctx->M; g.ldc = ctx->dh; g.batchC = (int64_t)ctx->dh * ctx->dh;
     g.accumulate = ctx->m_empty ? 0 : 1;
     g.ab_f16 = ctx->f32 ? 0 : 1;
+    const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
+    ctx->clk_wg[1] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
+    g.clk = ctx->clk_wg[1] ? ctx->clk[1] : nullptr;
     HIP_TRY(launch_gemm_nt(g, EPI_F32, ctx->heads, s));
   }
   {
@@ -532,6 +568,8 @@ conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T64, u
   const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
   hipStream_t s = ctx->stream;
   {
+  StageTimer whole(ctx, ST_QUANT, 1);
+  {
     StageTimer tm(ctx, ST_QROT);
     if (ctx->f32)
       HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
@@ -543,6 +581,7 @@ conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T64, u
   {
     StageTimer tm(ctx, ST_QERR);
     HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, ctx->row_sse, ctx->row_en, ctx->qsum, s));
+  }
   }
   double host[2] = {0.0, 0.0};
   HIP_TRY(hipMemcpyAsync(host, ctx->qsum, sizeof(host), hipMemcpyDeviceToHost, s));

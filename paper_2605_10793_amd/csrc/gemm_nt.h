@@ -54,10 +54,15 @@ struct GemmArgs {
   bf16_bits* Pt;           // EPI_XOUT: X' planes, transposed [n][m] (may be null)
   float* C32;              // EPI_XOUT: X' in fp32 [m][n] (may be null)
   const float* Xadd;       // EPI_XOUT: fp32 [m][n] added to acc before writing (may be null)
+  unsigned long long* clk; // optional clock probe, 4 values per workgroup (see gemm_num_workgroups): main-loop
+                           // shader cycles, then 100 MHz ticks of main loop, prologue, epilogue (may be null)
 };
 
 // Enqueue the GEMM on `stream`.  Returns hipSuccess or the launch error.
 hipError_t launch_gemm_nt(const GemmArgs& args, GemmEpilogue epi, int batch, hipStream_t stream);
+
+// Number of workgroups launch_gemm_nt uses for an M x N problem with `batch` entries (size of the clock probe / 4).
+int gemm_num_workgroups(int M, int N, int batch);
 
 // Per-batch-entry count of the partial sums the EPI_GRAMW epilogue writes for an M x N problem.
 int gemm_num_partials(int M, int N, int batch);

@@ -7,8 +7,8 @@
 // load-issue latencies.
 //
 // Operand path: HBM/L2 -> LDS directly (buffer_load ... lds, 16 bytes per lane, no
-// register staging), 2 LDS stages of 64 K-elements, fragments double buffered in
-// registers, one fence-free barrier per K step placed between MFMA groups.
+// register staging), 2 or 3 LDS stages of 64 K-elements (what fits in 160 KiB), fragments
+// double buffered in registers, one fence-free barrier per K step placed between MFMA groups.
 //
 // LDS layout: a tile row is 64 bf16 = 128 bytes = 8 chunks of 16 bytes; chunk c of row r
 // sits at physical chunk c ^ ((r >> 1) & 7), which spreads any 16 consecutive rows of
@@ -21,7 +21,6 @@ namespace conqur {
 namespace {
 
 constexpr int BK = 64;      // K elements per pipeline stage (one LDS tile row = 128 bytes = 8 chunks of 16 bytes)
-constexpr int NSTAGE = 2;   // LDS stages (2 x 64 KiB for the 256 x 256 tile); measured faster than 4 stages of 32
 
 __device__ __forceinline__ int lds_off(int row, int chunk) {
   return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
@@ -46,7 +45,7 @@ __device__ __forceinline__ void pipeline_barrier() { asm volatile("s_barrier" ::
 // the hardware returns zeros (also for loads whose destination is LDS).
 constexpr uint32_t kOobOffset = 0x80000000u;
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool F16>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs g, const int tiles_m, const int tiles_n) {
   constexpr int NW = WGM * WGN;                 // wavefronts per workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
@@ -55,6 +54,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   static_assert(NLA % NW == 0 && NLB % NW == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
   constexpr int STAGE = (BM + BN) * 128;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // Optional clock probe (g.clk != null): wall-clock ticks (100 MHz) of the prologue, main loop and epilogue
+  // of this workgroup and the shader-clock cycles of the main loop, from which the host derives the clock
+  // frequency the chip sustained while the MFMAs ran.
+  const unsigned long long pr_w0 = g.clk ? wall_clock64() : 0;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -177,6 +180,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   constexpr int LPT = QA + QB;   // loads per thread per tile
   constexpr int KS = BK / 16;    // MFMA K-substeps per tile
   constexpr int NMF = TM * TN;
+  constexpr int LQ0 = NMF - NMF / 2;   // loads issued behind the second half of a step's last substep; the rest of the
+                                       // tile's loads follow behind the first MFMAs of the next step
   static_assert(KS % 2 == 0, "fragment double buffering assumes an even number of substeps");
   bf16x8 fa[2][TM], fb[2][TN];
 
@@ -207,8 +212,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
 #pragma unroll
   for (int r = 0; r < TM + TN; ++r) read_frag(0, r, smem, 0);
 
+  const unsigned long long pr_w1 = g.clk ? wall_clock64() : 0, pr_c1 = g.clk ? clock64() : 0;
+  int stage = 0;   // it % NSTAGE
   for (int it = 0; it < nit; ++it) {
-    const int stage = it % NSTAGE;
+    const int prev_stage = stage == 0 ? NSTAGE - 1 : stage - 1, next_stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     const unsigned char* sa = smem + stage * STAGE;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
@@ -218,6 +225,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         for (int m = 0; m < NMF; ++m) {
           mfma(cur, m);
           if (m < TM + TN) read_frag(nxt, m, sa, kk + 1);
+          // the loads of tile it-1+NSTAGE that did not fit behind the previous step's last MFMAs
+          if (kk == 0 && it > 0 && LQ0 + m < LPT) issue_one(LQ0 + m, prev_stage);
           __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -230,7 +239,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         // tiles up to it+NSTAGE-1 have been issued; all but the newest NSTAGE-2 have landed => tile it+1 is in LDS
         wait_vmcnt<(NSTAGE - 2) * LPT>();
         pipeline_barrier();
-        const unsigned char* sn = smem + ((it + 1) % NSTAGE) * STAGE;
+        const unsigned char* sn = smem + next_stage * STAGE;
 #pragma unroll
         for (int r = 0; r < TM + TN; ++r) read_frag(nxt, r, sn, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -241,10 +250,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int q = NMF - NMF / 2; q < LPT; ++q) issue_one(q, stage);
+        for (int q = LQ0 + NMF; q < LPT; ++q) issue_one(q, stage);   // (none for the tile shapes in use)
       }
     }
+    stage = next_stage;
   }
+  const unsigned long long pr_w2 = g.clk ? wall_clock64() : 0, pr_c2 = g.clk ? clock64() : 0;
   wait_vmcnt<0>();   // drain the padding loads before the epilogue reuses nothing of LDS (keeps exit clean)
 
   // Accumulator element e = 4*j + i of tile (im, in) is output row
@@ -397,6 +408,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         }
       }
   }
+  if (g.clk) {
+    wait_vmcnt<0>();   // the epilogue's stores have left the wavefront
+    if (tid == 0) {
+      unsigned long long* o = g.clk + 4 * ((int64_t)blockIdx.z * gridDim.x + blockIdx.x);
+      o[0] = pr_c2 - pr_c1;
+      o[1] = pr_w2 - pr_w1;
+      o[2] = pr_w1 - pr_w0;
+      o[3] = wall_clock64() - pr_w2;
+    }
+  }
 }
 
 struct Tile { int bm, bn, wgm, wgn; float eff; };
@@ -416,11 +437,12 @@ int pick_tile(int M, int N, int batch) {
   return best;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool F16>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16>
 hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
+  static_assert(smem <= 160 * 1024, "LDS of one CU");
   static bool configured = false;
-  auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, EPI, F16>;
+  auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, NSTAGE, EPI, F16>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -435,11 +457,13 @@ hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
 template <int EPI, bool F16 = false>
 hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
   switch (pick_tile(a.M, a.N, batch)) {
-    case 0: return launch_one<256, 256, 2, 4, EPI, F16>(a, batch, stream);
-    case 1: return launch_one<256, 128, 4, 2, EPI, F16>(a, batch, stream);
-    case 2: return launch_one<128, 128, 2, 2, EPI, F16>(a, batch, stream);
-    case 4: return launch_one<192, 192, 3, 2, EPI, F16>(a, batch, stream);
-    default: return launch_one<64, 64, 2, 2, EPI, F16>(a, batch, stream);
+    // LDS stages: as many 64-deep tiles as fit (two of 64 KiB for 256 x 256; smaller tiles take a third, which
+    // puts two K steps instead of one between a load's issue and its use)
+    case 0: return launch_one<256, 256, 2, 4, 2, EPI, F16>(a, batch, stream);
+    case 1: return launch_one<256, 128, 4, 2, 3, EPI, F16>(a, batch, stream);
+    case 2: return launch_one<128, 128, 2, 2, 3, EPI, F16>(a, batch, stream);
+    case 4: return launch_one<192, 192, 3, 2, 3, EPI, F16>(a, batch, stream);
+    default: return launch_one<64, 64, 2, 2, 3, EPI, F16>(a, batch, stream);
   }
 }
 
@@ -448,6 +472,11 @@ hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
 int gemm_num_partials(int M, int N, int batch) {
   const Tile& t = kTiles[pick_tile(M, N, batch)];
   return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * t.wgm * t.wgn;
+}
+
+int gemm_num_workgroups(int M, int N, int batch) {
+  const Tile& t = kTiles[pick_tile(M, N, batch)];
+  return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
 }
 
 int gemm_sign_slabs(int M, int N, int batch) {
