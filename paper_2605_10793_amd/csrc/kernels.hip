@@ -1,6 +1,8 @@
 // Non-GEMM kernels of the calibration path (see kernels.h).
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace conqur {
 
 namespace {
@@ -46,18 +48,36 @@ __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, i
   const int h = (int)(gw - i * heads);
   float ss = 0.0f;
   if constexpr (F32) {
+    // four independent 16-byte loads per lane in flight (a row is read once, so the loop is latency bound otherwise)
     const float* x = reinterpret_cast<const float*>(X) + i * stride + (int64_t)h * dh;
-    for (int c = lane; c < dh / 4; c += 64) {
-      const float4 v = *reinterpret_cast<const float4*>(x + c * 4);
-      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    const int nc = dh / 4;
+    for (int c0 = lane; c0 < nc; c0 += 256) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = c0 + u * 64;
+        v[u] = c < nc ? *reinterpret_cast<const float4*>(x + c * 4) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) ss += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
     }
   } else {
     const bf16_bits* x = reinterpret_cast<const bf16_bits*>(X) + i * stride + (int64_t)h * dh;
-    for (int c = lane; c < dh / 8; c += 64) {
-      float f[8];
-      unpack8(*reinterpret_cast<const uint4*>(x + c * 8), f);
+    const int nc = dh / 8;
+    for (int c0 = lane; c0 < nc; c0 += 256) {
+      uint4 v[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+      for (int u = 0; u < 4; ++u) {
+        const int c = c0 + u * 64;
+        v[u] = c < nc ? *reinterpret_cast<const uint4*>(x + c * 8) : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float f[8];
+        unpack8(v[u], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+      }
     }
   }
   ss = wave_sum(ss);
@@ -79,7 +99,10 @@ template <bool F32, int NP>
 __global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict__ X, int64_t T, int64_t stride, int d, int dh,
                                                          const float* __restrict__ w, int64_t ldn,
                                                          bf16_bits* __restrict__ Xt, int64_t pitch, int64_t plane) {
-  __shared__ float tile[64][65];
+  // bf16 input: the tile holds the finished fp16 values (8.3 KiB, so that this kernel's workgroups still fit
+  // beside a GEMM workgroup that owns 144 KiB of the CU's LDS); fp32 input: fp32 values, split after the transpose
+  using TileT = typename std::conditional<NP == 1, bf16_bits, float>::type;
+  __shared__ TileT tile[64][NP == 1 ? 66 : 65];
   const int64_t i0 = (int64_t)blockIdx.x * 64;
   const int k0 = blockIdx.y * 64;
   const int t = threadIdx.x;
@@ -107,7 +130,10 @@ __global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict_
         for (int e = 0; e < 8; ++e) f[e] = (wi != 0.0f) ? f[e] * wi : 0.0f;
       }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) tile[r][c * 8 + e] = f[e];
+      for (int e = 0; e < 8; ++e) {
+        if constexpr (NP == 1) tile[r][c * 8 + e] = f32_to_f16(f[e]);   // |x^| <= 1: fp16 keeps 11 significant bits
+        else tile[r][c * 8 + e] = f[e];
+      }
     }
   }
   __syncthreads();
@@ -122,7 +148,7 @@ __global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict_
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         if constexpr (NP == 1) {
-          out[0][e] = f32_to_f16(tile[tc * 8 + e][kl]);  // |x^| <= 1: fp16 keeps 11 significant bits
+          out[0][e] = tile[tc * 8 + e][kl];
         } else {
           bf16_bits p[NP];
           split_bf16<NP>(tile[tc * 8 + e][kl], p);
