@@ -60,6 +60,10 @@ typedef struct {
                                directions with small singular values), 1 = two bf16 planes per operand
                                (about 16 significant bits), 2 = three planes (fp32-equivalent products).
                                The closing iterations always run fp32-equivalent.                     */
+  uint32_t polar_verify;    /* orthogonality of the final iterate: 0 = bounded from the last measured
+                               residual (exact-arithmetic residual of the closing step, from ||D^3||_F,
+                               plus a rounding allowance; one bf16 GEMM), 1 = measured by one more
+                               fp32-equivalent Gram matrix (costs about six bf16 GEMMs)               */
   int32_t device;           /* HIP device ordinal                                                   */
   void* stream;             /* hipStream_t the caller owns (NULL = the device's default stream)      */
 } conqur_config;
@@ -76,10 +80,13 @@ typedef struct {
 typedef struct {
   uint32_t iters;       /* polar iterations run (main + closing)                                   */
   uint32_t accurate;    /* how many of them were closing iterations (fp32-equivalent Gram)         */
-  double orth_err;      /* ||R^T R - I||_F of the stored fp32 R, as measured on the device          */
+  double orth_err;      /* ||R^T R - I||_F of the stored fp32 R: measured on the device, or an upper
+                           estimate of it (see polar_verify)                                         */
   double inner;         /* <R_new, M>, the Procrustes objective value (nuclear norm at the optimum)  */
   double m_fro;         /* ||M||_F                                                                  */
   double ms;            /* device time of this update in milliseconds (all heads together)          */
+  uint32_t orth_measured; /* 1: orth_err was measured; 0: it is the estimate                          */
+  uint32_t reserved;
 } conqur_update_stats;
 
 /*

@@ -31,7 +31,7 @@ class Config(ctypes.Structure):
     _fields_ = [("d", ctypes.c_uint32), ("heads", ctypes.c_uint32), ("act_dtype", ctypes.c_uint32),
                 ("max_tokens", ctypes.c_uint32), ("prox_lambda", ctypes.c_float), ("polar_tol", ctypes.c_float),
                 ("polar_max_iters", ctypes.c_uint32), ("polar_precision", ctypes.c_uint32),
-                ("device", ctypes.c_int32), ("stream", ctypes.c_void_p)]
+                ("polar_verify", ctypes.c_uint32), ("device", ctypes.c_int32), ("stream", ctypes.c_void_p)]
 
 
 class BatchStats(ctypes.Structure):
@@ -40,7 +40,8 @@ class BatchStats(ctypes.Structure):
 
 class UpdateStats(ctypes.Structure):
     _fields_ = [("iters", ctypes.c_uint32), ("accurate", ctypes.c_uint32), ("orth_err", ctypes.c_double),
-                ("inner", ctypes.c_double), ("m_fro", ctypes.c_double), ("ms", ctypes.c_double)]
+                ("inner", ctypes.c_double), ("m_fro", ctypes.c_double), ("ms", ctypes.c_double),
+                ("orth_measured", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class ConqurError(RuntimeError):
@@ -100,14 +101,14 @@ class Calibrator:
 
     def __init__(self, d: int, heads: int, dtype: str, R0: np.ndarray, max_tokens: int,
                  prox_lambda: float = 0.0, polar_tol: float = 0.0, polar_max_iters: int = 0, polar_precision: int = 0,
-                 device: int = 0, stream: Optional[int] = None):
+                 polar_verify: int = 0, device: int = 0, stream: Optional[int] = None):
         import torch
         self._lib = load()
         self.d, self.heads, self.dh, self.dtype = d, heads, d // max(heads, 1), dtype
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
         cfg = Config(d, heads, BF16 if dtype == "bf16" else F32, max_tokens, prox_lambda, polar_tol,
-                     polar_max_iters, polar_precision, device, ctypes.c_void_p(stream))
+                     polar_max_iters, polar_precision, polar_verify, device, ctypes.c_void_p(stream))
         R0 = np.ascontiguousarray(R0, dtype=np.float32)
         if R0.size != heads * self.dh * self.dh:
             raise ValueError("R0 must hold heads * dh * dh floats")
@@ -158,7 +159,8 @@ class Calibrator:
         arr = (UpdateStats * self.heads)()
         st = self._check(self._lib.conqur_update_rotation(self._h, arr), allow)
         return st, [dict(iters=int(a.iters), accurate=int(a.accurate), orth_err=float(a.orth_err),
-                         inner=float(a.inner), m_fro=float(a.m_fro), ms=float(a.ms)) for a in arr]
+                         inner=float(a.inner), m_fro=float(a.m_fro), ms=float(a.ms),
+                         orth_measured=bool(a.orth_measured)) for a in arr]
 
     def quant_error(self, X, bits: int = 4) -> Tuple[float, float]:
         p, T, stride = self._x(X)

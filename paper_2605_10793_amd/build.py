@@ -15,7 +15,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          # the default lowers them to compare-and-swap loops, which crawl under contention
          "-munsafe-fp-atomics",
          # keep the compiler from forming packed-fp32 instructions
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # per-kernel register / scratch report, read below: a GEMM kernel that spills runs at half speed
+         "-Rpass-analysis=kernel-resource-usage"]
 
 
 def hipcc() -> str:
@@ -23,6 +25,19 @@ def hipcc() -> str:
         if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
             return c
     return "hipcc"
+
+
+def kernels_with_scratch(remarks: str):
+    """(kernel, bytes per lane) for every kernel the compiler's resource report shows with private scratch memory."""
+    found, name = [], None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line and name:
+            n = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0].strip())
+            if n:
+                found.append((name, n))
+    return found
 
 
 def build_lib(verbose: bool = False) -> str:
@@ -38,9 +53,13 @@ def build_lib(verbose: bool = False) -> str:
     objs = []
     for src, obj, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        spills = kernels_with_scratch(out)
+        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
         if p.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        for name, nbytes in spills:
+            print(f"build.py: WARNING {src}: kernel {name} uses {nbytes} bytes/lane of scratch (register spill)",
+                  file=sys.stderr, flush=True)
         if verbose and out.strip():
             print(out)
         objs.append(obj)

@@ -27,6 +27,10 @@ constexpr SegList kSeg6 = {6, {2, 1, 0, 1, 0, 0}, {0, 1, 2, 0, 1, 0}};  // all t
 constexpr SegList kSeg3x1 = {3, {2, 1, 0}, {0, 0, 0}};                   // 3-plane left operand, exact right operand
 
 constexpr int kResidSlots = 512;
+// Rounding share of ||X^T X - I||_F after a closing step, per unit of dh (correction product from two-plane
+// operands, fp32 iterate): used where the residual is predicted instead of measured.
+constexpr double kOrthFloorPerDim = 1e-8;
+constexpr double kCubeFactor = 5.5;
 constexpr int kClkMaxWorkgroups = 8192;   // clock probes are taken for GEMM launches of at most this many workgroups
 
 enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_STEP, ST_QUANT, ST_COUNT };
@@ -174,7 +178,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   const uint32_t dh = cfg->d / cfg->heads;
   if (dh % 16 || dh > 8192 || cfg->d > 65536) return CONQUR_EINVAL;
   if (cfg->act_dtype != CONQUR_F32 && cfg->act_dtype != CONQUR_BF16) return CONQUR_EINVAL;
-  if (cfg->max_tokens == 0 || cfg->max_tokens > (1u << 22) || cfg->polar_precision > 2) return CONQUR_EINVAL;
+  if (cfg->max_tokens == 0 || cfg->max_tokens > (1u << 22) || cfg->polar_precision > 2 || cfg->polar_verify > 1) return CONQUR_EINVAL;
   if (!(cfg->prox_lambda >= 0.0f) || !(cfg->polar_tol >= 0.0f)) return CONQUR_EINVAL;
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return CONQUR_EHIP;
@@ -433,7 +437,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     return e;
   };
   // W2 = D + 1.5 D^2 from the planes of D = (I - G)/2 in PW (D is symmetric, so D D^T = D^2)
-  auto square_correction = [&]() -> hipError_t {
+  auto square_correction = [&](bool keep_square) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     g.A = ctx->PW; g.B = ctx->PW; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
@@ -441,7 +445,23 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.nseg = 1;   // D^2 is second order small: single bf16 planes are ample
     g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW2; g.np_out = 2; g.plane_out = plane;
     g.Padd = ctx->PW; g.np_add = 2; g.coef_i = 0.0f; g.coef_g = 1.5f;
-    return launch_gemm_nt(g, EPI_GRAMW, h, s);
+    if (!keep_square) return launch_gemm_nt(g, EPI_GRAMW, h, s);
+    g.Pacc = ctx->PW2 + 2 * plane;   // D^2 itself, third plane of the buffer
+    return launch_gemm_nt(g, EPI_SQUARE, h, s);
+  };
+  // ||D^3||_F^2 (into residual slot `slot`) from the planes of D and D^2: the quintic step leaves the residual
+  // I - X'^T X' = 5 D^3 + 3.75 D^4 + 4.5 D^5 (both sides polynomials in D), so this norm predicts it.
+  auto cube_norm = [&]() -> hipError_t {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ctx->PW; g.B = ctx->PW2 + 2 * plane; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
+    g.M = g.N = g.K = dh;
+    g.nseg = 1;
+    g.ldc = dh; g.batchC = blk; g.plane_out = plane;
+    g.resid_part = ctx->resid_part;
+    hipError_t e = launch_gemm_nt(g, EPI_FRO2, h, s);
+    if (e == hipSuccess) e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);
+    return e;
   };
   std::vector<double> hist((size_t)kResidSlots * h);
   auto read_resid = [&](int sl_idx, double* worst) -> conqur_status {
@@ -488,7 +508,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // X <- X + X (D + 1.5 D^2) (quintic, error e -> O(e^3): one step takes the bf16 floor of the
   // main phase to the fp32 floor).  The correction is small, so two planes per operand
   // suffice for the product; the fp32 iterate is added in the epilogue.
-  bool converged = false;
+  bool converged = false, predicted = false;
   int kicks = 0;
   double res = 0.0;
   int last_slot = 0;
@@ -518,12 +538,38 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       continue;
     }
     const bf16_bits* W = ctx->PW;
-    if (res <= 1e-2 * std::sqrt((double)dh)) {   // rms deviation of the singular values below 1e-2
-      HIP_TRY(square_correction());
+    const bool quintic = res <= 1e-2 * std::sqrt((double)dh);   // rms deviation of the singular values below 1e-2
+    const bool predict = quintic && (!ctx->cfg.polar_verify || trace);
+    if (quintic) {
+      HIP_TRY(square_correction(predict));
       W = ctx->PW2;
     }
     HIP_TRY(apply(kSeg3, W, 3, 2, true, true));
     ++iters; ++closing;
+    if (predict) {
+      // Orthogonality of the corrected iterate without another fp32-equivalent Gram matrix: the exact-arithmetic
+      // residual of the quintic step, 5 ||D^3||_F (1 + 0.75 rho + 0.9 rho^2) with rho = ||D||_2 <= 0.05 here
+      // (kCubeFactor = 5.5 also covers the bf16 rounding of the D^3 product),
+      // plus the rounding of the correction product and of the fp32 iterate (kOrthFloor per unit of dh,
+      // calibrated against the measured residual).
+      HIP_TRY(cube_norm());
+      const int cslot = slot++;
+      double d3 = 0.0;
+      st = read_resid(cslot, &d3);
+      if (st != CONQUR_OK) return st;
+      const double pred = kCubeFactor * d3 + kOrthFloorPerDim * dh;
+      if (trace) std::fprintf(stderr, "[conqur] polar closing: ||D^3||_F=%.4e predicted resid_F=%.4e\n", d3, pred);
+      if (!ctx->cfg.polar_verify && std::isfinite(pred) && pred <= tol) {
+        for (int q = 0; q < h; ++q) {
+          const double d3q = std::sqrt(hist[(size_t)cslot * h + q]);
+          hist[(size_t)cslot * h + q] = (kCubeFactor * d3q + kOrthFloorPerDim * dh) * (kCubeFactor * d3q + kOrthFloorPerDim * dh);
+        }
+        last_slot = cslot;
+        converged = true;
+        predicted = true;
+        break;
+      }
+    }
   }
 
   HIP_TRY(launch_polar_finish(ctx->PX, ctx->M, h, blk, ctx->R, ctx->inner, s));
@@ -548,7 +594,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     float ms = 0.0f;
     HIP_TRY(hipEventElapsedTime(&ms, ctx->ev[ST_UPDATE][0], ctx->ev[ST_UPDATE][1]));
     for (int q = 0; q < h; ++q) {
-      out[q].iters = iters; out[q].accurate = closing;
+      out[q].iters = iters; out[q].accurate = closing; out[q].orth_measured = predicted ? 0u : 1u;
       out[q].orth_err = std::sqrt(hist[(size_t)last_slot * h + q]);
       out[q].inner = inner[q]; out[q].m_fro = std::sqrt(fro2[q]); out[q].ms = ms;
     }

@@ -18,6 +18,9 @@ enum GemmEpilogue : int {
                  // (natural layout) and per-wavefront partial sums of (G - I)^2
   EPI_XOUT = 4,  // acc = X' (+ Xadd): written as fp32 (C32) and/or np_out bf16 split planes in natural (Pn)
                  // and transposed (Pt) layout -- the operands of the next Gram / apply GEMMs
+  EPI_SQUARE = 5, // acc = D^2 (D symmetric, given as two planes Padd): writes acc as one bf16 plane (Pacc) and
+                  // coef_g * acc + D as two split planes (Pn)
+  EPI_FRO2 = 6,   // per-wavefront partial sums of acc^2 only (resid_part): a Frobenius norm, nothing stored
 };
 
 constexpr int kMaxSegments = 6;
@@ -54,6 +57,7 @@ struct GemmArgs {
   bf16_bits* Pt;           // EPI_XOUT: X' planes, transposed [n][m] (may be null)
   float* C32;              // EPI_XOUT: X' in fp32 [m][n] (may be null)
   const float* Xadd;       // EPI_XOUT: fp32 [m][n] added to acc before writing (may be null)
+  bf16_bits* Pacc;         // EPI_SQUARE: the accumulator itself as one bf16 plane [m][n]
   unsigned long long* clk; // optional clock probe, 4 values per workgroup (see gemm_num_workgroups): main-loop
                            // shader cycles, then 100 MHz ticks of main loop, prologue, epilogue (may be null)
 };

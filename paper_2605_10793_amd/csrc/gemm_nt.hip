@@ -369,6 +369,45 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
       rsum = wave_sum_d(rsum);
       if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
     }
+  } else if constexpr (EPI == EPI_SQUARE) {
+    const int64_t boff = (int64_t)bz * g.batchC;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = nw + j * 32 + col;
+        if (n >= g.N) continue;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (m >= g.M) continue;
+          const int64_t off = boff + (int64_t)m * g.ldc + n;
+          const float a = acc[i][j][e];
+          g.Pacc[off] = f32_to_bf16(a);
+          float w = g.coef_g * a + bf16_to_f32(g.Padd[off]) + bf16_to_f32(g.Padd[g.plane_out + off]);
+          const bf16_bits h0 = f32_to_bf16(w);
+          g.Pn[off] = h0;
+          g.Pn[g.plane_out + off] = f32_to_bf16(w - bf16_to_f32(h0));
+        }
+      }
+  } else if constexpr (EPI == EPI_FRO2) {
+    double rsum = 0.0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = nw + j * 32 + col;
+        if (n >= g.N) continue;
+        float part = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (m < g.M) part += acc[i][j][e] * acc[i][j][e];
+        }
+        rsum += (double)part;
+      }
+    rsum = wave_sum_d(rsum);
+    if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
   } else {  // EPI_XOUT
     const int64_t boff = (int64_t)bz * g.batchC;
 #pragma unroll
@@ -494,6 +533,8 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
     case EPI_F32: return a.ab_f16 ? launch_epi<EPI_F32, true>(a, batch, stream) : launch_epi<EPI_F32>(a, batch, stream);
     case EPI_GRAMW: return launch_epi<EPI_GRAMW>(a, batch, stream);
     case EPI_XOUT: return launch_epi<EPI_XOUT>(a, batch, stream);
+    case EPI_SQUARE: return launch_epi<EPI_SQUARE>(a, batch, stream);
+    case EPI_FRO2: return launch_epi<EPI_FRO2>(a, batch, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -32,7 +32,7 @@ def test_config_struct_matches_header_field_order():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"\b(?:uint32_t|int32_t|float|void\*)\s+([a-z_]+);", body)
     assert fields == [f[0] for f in binding.Config._fields_]
-    assert ctypes.sizeof(binding.Config) == 9 * 4 + 4 + 8   # nine 32-bit fields, padding, one pointer
+    assert ctypes.sizeof(binding.Config) == 10 * 4 + 8   # ten 32-bit fields, one pointer
 
 
 def test_null_arguments_are_rejected_without_a_device():
@@ -42,12 +42,14 @@ def test_null_arguments_are_rejected_without_a_device():
     assert lib.conqur_step_batch(None, None, 1, 1) == binding.EINVAL
     assert lib.conqur_update_rotation(None, None) == binding.EINVAL
     lib.conqur_destroy(None)
-    bad = binding.Config(60, 1, binding.BF16, 8, 0.0, 0.0, 0, 0, 0, None)     # dh % 16 != 0
+    bad = binding.Config(60, 1, binding.BF16, 8, 0.0, 0.0, 0, 0, 0, 0, None)     # dh % 16 != 0
     R0 = np.eye(60, dtype=np.float32)
     assert lib.conqur_init(ctypes.byref(bad), R0.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == binding.EINVAL
-    bad = binding.Config(64, 1, 7, 8, 0.0, 0.0, 0, 0, 0, None)                # unknown dtype
+    bad = binding.Config(64, 1, 7, 8, 0.0, 0.0, 0, 0, 0, 0, None)                # unknown dtype
     assert lib.conqur_init(ctypes.byref(bad), R0.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == binding.EINVAL
-    bad = binding.Config(64, 1, binding.BF16, 8, 0.0, 0.0, 0, 3, 0, None)     # polar_precision > 2
+    bad = binding.Config(64, 1, binding.BF16, 8, 0.0, 0.0, 0, 3, 0, 0, None)     # polar_precision > 2
+    assert lib.conqur_init(ctypes.byref(bad), R0.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == binding.EINVAL
+    bad = binding.Config(64, 1, binding.BF16, 8, 0.0, 0.0, 0, 0, 2, 0, None)     # polar_verify > 1
     assert lib.conqur_init(ctypes.byref(bad), R0.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == binding.EINVAL
 
 
@@ -67,3 +69,12 @@ def test_input_streams_are_reproducible_and_shaped():
     R0 = I.initial_rotation(w4)
     assert R0.shape == (32, 128, 128)
     assert np.abs(R0[5].T.astype(np.float64) @ R0[5] - np.eye(128)).max() < 1e-5
+
+
+def test_build_reports_register_spills():
+    from paper_2605_10793_amd import build
+    remarks = ("a.hip:1:1: remark: Function Name: kern_a [-Rpass-analysis=kernel-resource-usage]\n"
+               "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+               "a.hip:9:1: remark: Function Name: kern_b [-Rpass-analysis=kernel-resource-usage]\n"
+               "a.hip:9:1: remark:     ScratchSize [bytes/lane]: 576 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert build.kernels_with_scratch(remarks) == [("kern_b", 576)]

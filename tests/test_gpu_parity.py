@@ -89,13 +89,18 @@ def compare_update(B, cal, oc, w, tag, check_R):
         say(f"  {tag} head {h}: iters={st_g[h]['iters']} (accurate {st_g[h]['accurate']}) orth={orth:.2e} "
             f"dev_orth={st_g[h]['orth_err']:.2e} <R,A> gpu={got:.6e} oracle={best:.6e} ms={st_g[h]['ms']:.3f}")
         assert orth <= TOL_ORTH, (tag, h, orth)
+        # the device's figure: a measurement (within its own rounding of the fp64 value) or an upper estimate
+        if st_g[h]["orth_measured"]:
+            assert abs(st_g[h]["orth_err"] - orth) <= 0.35 * orth + 2e-7, (tag, h)
+        else:
+            assert orth <= st_g[h]["orth_err"] <= 8e-5, (tag, h, orth, st_g[h]["orth_err"])
         assert abs(got - best) <= TOL_REL * abs(best), (tag, h, got, best)
         assert abs(st_g[h]["inner"] - inner_g) <= 1e-4 * abs(inner_g) + 1e-6
         assert abs(st_g[h]["m_fro"] - np.linalg.norm(M[h])) <= 1e-5 * np.linalg.norm(M[h])
         if check_R:
             dR = np.abs(Rg[h] - oc.R[h]).max()
             say(f"  {tag} head {h}: max|R - R_oracle| = {dR:.2e}")
-            assert dR <= 2e-2, (tag, h, dR)
+            assert dR <= (2e-2 if check_R is True else check_R), (tag, h, dR)
     return rc
 
 
@@ -107,11 +112,11 @@ def compare_quant(B, cal, oc, X, w, tag):
     assert abs(en_g - en_o) <= TOL_REL * en_o
 
 
-def run_stream(B, w, n_batches, check_R, tokens=None):
+def run_stream(B, w, n_batches, check_R, tokens=None, **cal_kwargs):
     R0 = I.initial_rotation(w)
     T = w.tokens_per_batch if tokens is None else tokens
     oc = O.OracleCalibrator(w.d, w.heads, w.dtype, R0, w.prox_lambda)
-    cal = B.Calibrator(w.d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
+    cal = B.Calibrator(w.d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda, **cal_kwargs)
     try:
         for b in range(n_batches):
             X = I.batch(w, b, T)
@@ -142,6 +147,42 @@ def test_small_streams(B, d, T, heads, dtype, lam):
     w = I.small_workload(d, T, n_batches=2, heads=heads, dtype=dtype, seed=100 + d + T, prox_lambda=lam,
                          massive_frac=0.01)
     run_stream(B, w, 2, check_R=lam > 0)
+
+
+@pytest.mark.parametrize("precision,verify", [(0, 1), (1, 0), (2, 1)])
+def test_polar_options(B, precision, verify):
+    """The other arithmetic modes of the update (two / three operand planes in the main phase) and the measured
+    orthogonality check, on a stream with the proximal reading (R itself is compared with the oracle's)."""
+    w = I.small_workload(384, 300, n_batches=2, seed=911, prox_lambda=0.1, massive_frac=0.01)
+    # measured: 2e-3 / 4e-6 / 2e-7 -- rounding of the main phase, amplified by 1/sigma on the weak directions
+    run_stream(B, w, 2, check_R={0: 2e-2, 1: 5e-5, 2: 5e-6}[precision], polar_precision=precision, polar_verify=verify)
+
+
+def test_polar_precision_improves_R(B):
+    """Planted polar factor with condition number 1e3: the entrywise error of R falls with the operand precision of
+    the main phase (rounding on a direction is amplified by 1/sigma)."""
+    d = 512
+    Q = I.random_orthogonal(d, 43)
+    sig = np.logspace(0, -3, d)
+    P, _ = I.spd_with_spectrum(d, sig, 44)
+    A = (Q @ P).astype(np.float32)
+    errs = []
+    for precision in (0, 1, 2):
+        cal = B.Calibrator(d, 1, "bf16", np.eye(d, dtype=np.float32), max_tokens=64, polar_precision=precision)
+        try:
+            cal.set_state(M=A)
+            rc, st = cal.update_rotation()
+            R, _, _ = cal.get_state(want_M=False)
+            R64 = R[0].astype(np.float64)
+            errs.append(np.abs(R64 - Q).max())
+            say(f"  precision {precision}: iters={st[0]['iters']} orth={np.linalg.norm(R64.T @ R64 - np.eye(d)):.2e} "
+                f"max|R-Q|={errs[-1]:.2e} ms={st[0]['ms']:.2f}")
+            assert np.linalg.norm(R64.T @ R64 - np.eye(d)) <= TOL_ORTH
+            assert abs((R64 * A).sum() - sig.sum()) <= TOL_REL * sig.sum()
+        finally:
+            cal.close()
+    assert errs[1] <= 0.5 * errs[0] and errs[2] <= errs[1] * 1.05
+    assert errs[2] <= 1e-4
 
 
 def test_c4_heads_reduced_tokens(B):
