@@ -72,6 +72,7 @@ struct conqur_ctx {
   double* resid_part = nullptr;                      // [heads][parts] per-wavefront partials of one Gram GEMM
   int resid_parts = 0;
   double *fro2 = nullptr, *inner = nullptr;          // [heads]
+  double* dot_part = nullptr;                        // [heads][(dh/64)^2] per-tile partials of <R, M>
   int64_t last_T = 0;
 
   int timing = 0;   // 0 off, 1 whole-call events, 2 per-stage events and GEMM clock probes as well
@@ -211,9 +212,10 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   A(dev_alloc(ctx, &ctx->nrm, (size_t)ctx->heads * tmax));
   A(dev_alloc(ctx, &ctx->w, (size_t)ctx->heads * tmax));
   A(dev_alloc(ctx, &ctx->Lpart, (size_t)ctx->heads * ctx->slabs_max * tmax));
-  A(dev_alloc(ctx, &ctx->L, (size_t)ctx->heads));
-  A(dev_alloc(ctx, &ctx->rows, (size_t)ctx->heads));
-  A(dev_alloc(ctx, &ctx->skipped, (size_t)ctx->heads));
+  // L, rows, skipped share one allocation so that one fill clears the batch statistics
+  A(dev_alloc(ctx, &ctx->L, (size_t)3 * ctx->heads));
+  ctx->rows = reinterpret_cast<unsigned long long*>(ctx->L + ctx->heads);
+  ctx->skipped = ctx->rows + ctx->heads;
   A(dev_alloc(ctx, &ctx->nonfinite, (size_t)4));
   A(dev_alloc(ctx, reinterpret_cast<char**>(&ctx->Y), tmax * d * (ctx->f32 ? 4 : 2)));
   A(dev_alloc(ctx, &ctx->row_sse, tmax));
@@ -229,6 +231,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   A(dev_alloc(ctx, &ctx->resid, (size_t)kResidSlots * ctx->heads));
   ctx->resid_parts = gemm_num_partials((int)dh, (int)dh, ctx->heads);
   A(dev_alloc(ctx, &ctx->resid_part, (size_t)ctx->resid_parts * ctx->heads));
+  A(dev_alloc(ctx, &ctx->dot_part, (size_t)ctx->heads * pack_dot_partials(ctx->dh)));
   A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
   A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
   for (int k = 0; k < 2; ++k) A(dev_alloc(ctx, &ctx->clk[k], (size_t)4 * kClkMaxWorkgroups));
@@ -392,16 +395,17 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][0], s));
 
   HIP_TRY(launch_fill_zero(ctx->fro2, h * sizeof(double), s));
-  HIP_TRY(launch_fill_zero(ctx->inner, h * sizeof(double), s));
   HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->fro2, s));
-  // X0 = (M + lambda tau R) / alpha, alpha = ||M||_F (1 + lambda) >= ||X0||_2
-  HIP_TRY(launch_polar_start(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, ctx->PX, s));
 
   const int np_main = 1 + (int)ctx->cfg.polar_precision;
   const SegList& seg_main = np_main == 1 ? kSeg1 : (np_main == 2 ? kSeg3 : kSeg6);
   const uint32_t cap = ctx->cfg.polar_max_iters;
   const double tol = ctx->cfg.polar_tol;
   int cur = 0;            // which ping-pong plane buffer holds the iterate
+  // X0 = (M + lambda tau R) / alpha, alpha = ||M||_F (1 + lambda) >= ||X0||_2, written straight as the operand
+  // planes of the first step (no fp32 copy: at least one main step runs, and the last one writes the fp32 iterate)
+  HIP_TRY(launch_polar_start_pack(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, np_main, nullptr,
+                                  ctx->PXn[cur], ctx->PXt[cur], plane, s));
   int slot = 0;           // next residual-history slot
   uint32_t iters = 0, closing = 0;
 
@@ -421,7 +425,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   };
   // X' = X W (+ X): reads the planes in buffer `cur`, writes np_x planes (both layouts)
   // into the other buffer, and the fp32 iterate when asked.
-  auto apply = [&](const SegList& sl, const bf16_bits* W, int np_t, int np_n, bool add_x, bool write_f32) -> hipError_t {
+  auto apply = [&](const SegList& sl, const bf16_bits* W, int np_t, int np_n, bool add_x, float* out32) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     g.A = ctx->PXn[cur]; g.B = W; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
@@ -431,7 +435,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.ldc = dh; g.batchC = blk; g.np_out = np_t; g.np_out_n = np_n; g.plane_out = plane;
     g.Pn = ctx->PXn[cur ^ 1]; g.Pt = ctx->PXt[cur ^ 1];
     g.Xadd = add_x ? ctx->PX : nullptr;
-    g.C32 = write_f32 ? ctx->PX : nullptr;
+    g.C32 = out32;
     hipError_t e = launch_gemm_nt(g, EPI_XOUT, h, s);
     cur ^= 1;
     return e;
@@ -478,8 +482,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // The singular values of X0 lie in [l, 1]; l is the value the proximal term guarantees
   // on the null space of M, halved.  (Smaller ones still grow by the factor a > 2.5 per
   // step and are finished by the closing iterations.)
-  auto main_phase = [&](double l0) -> conqur_status {
-    HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s));
+  auto main_phase = [&](double l0, bool planes_ready) -> conqur_status {
+    if (!planes_ready) HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s));
     const double e_stop = np_main == 1 ? 4e-3 : 5e-4;   // the safety margins below floor the ripple near 2e-4
     double l = l0, u = 1.0;
     for (int k = 0; k < 64 && iters < cap && slot < kResidSlots - 8; ++k) {
@@ -490,7 +494,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       ++slot;
       // the last main step hands over to the closing iterations: fp32 iterate, 3 transposed planes for
       // the fp32-equivalent Gram matrix, 2 natural planes for the correction product
-      HIP_TRY(apply(seg_main, ctx->PW, last ? 3 : np_main, last ? 2 : np_main, false, last));
+      HIP_TRY(apply(seg_main, ctx->PW, last ? 3 : np_main, last ? 2 : np_main, false, last ? ctx->PX : nullptr));
       ++iters;
       if (trace) std::fprintf(stderr, "[conqur] polar main step %d: [l,u]=[%.3e,%.3f] a=%.4f b=%.4f ripple=%.3e planes=%d\n", k, l, u, a, b, E, np_main);
       if (last) break;
@@ -500,7 +504,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     return CONQUR_OK;
   };
   const double lam_eff = std::max((double)ctx->cfg.prox_lambda, 9.5367431640625e-07);
-  conqur_status st = main_phase(0.5 * lam_eff / ((1.0 + lam_eff) * std::sqrt((double)dh)));
+  conqur_status st = main_phase(0.5 * lam_eff / ((1.0 + lam_eff) * std::sqrt((double)dh)), true);
   if (st != CONQUR_OK) return st;
 
   // ---- closing iterations, Gram matrix in fp32-equivalent arithmetic (3 planes, 6 products).
@@ -512,8 +516,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   int kicks = 0;
   double res = 0.0;
   int last_slot = 0;
-  if (iters == 0 || cap <= iters)   // no main step ran (or the cap cut it): planes of the fp32 iterate
-    HIP_TRY(launch_pack(ctx->PX, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
+  const float* final_x = ctx->PX;   // where the final iterate lives (the lean closing step writes R directly)
   while (true) {
     HIP_TRY(gram(kSeg6, 0.5f, -0.5f, 2, true));
     last_slot = slot++;
@@ -523,7 +526,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     if (!std::isfinite(res)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
     if (res <= tol) { converged = true; break; }
     if (iters >= cap || slot >= kResidSlots - 8) break;
-    if (res > 0.7 && kicks < 2 && iters + 8 < cap) {
+    if (res > 0.7 && kicks < 2 && iters + 8 < cap && final_x == ctx->PX) {
       // Some singular values are still (near) zero: either far below the assumed bound or
       // pinned there by an exact symmetry of M (identical columns, which identical
       // corner-sign columns produce and which the iteration, rounding included,
@@ -533,7 +536,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       const double kappa = np_main == 1 ? 1.0 / 64.0 : 1.0 / 256.0;
       HIP_TRY(launch_axpy(ctx->PX, ctx->R, plane, (float)kappa, s));
       ++kicks;
-      st = main_phase(0.25 * kappa / std::sqrt((double)dh));
+      st = main_phase(0.25 * kappa / std::sqrt((double)dh), false);
       if (st != CONQUR_OK) return st;
       continue;
     }
@@ -544,7 +547,15 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       HIP_TRY(square_correction(predict));
       W = ctx->PW2;
     }
-    HIP_TRY(apply(kSeg3, W, 3, 2, true, true));
+    // lean: the step is expected to be the last one -- no operand planes for a further Gram / apply, and the
+    // result goes straight into R
+    const bool lean = predict && !ctx->cfg.polar_verify;
+    if (final_x != ctx->PX) {   // an earlier lean step was not the last after all: continue from its result
+      HIP_TRY(hipMemcpyAsync(ctx->PX, ctx->R, (size_t)plane * sizeof(float), hipMemcpyDeviceToDevice, s));
+      final_x = ctx->PX;
+    }
+    HIP_TRY(apply(kSeg3, W, lean ? 0 : 3, lean ? 0 : 2, true, lean ? ctx->R : ctx->PX));
+    if (lean) final_x = ctx->R;
     ++iters; ++closing;
     if (predict) {
       // Orthogonality of the corrected iterate without another fp32-equivalent Gram matrix: the exact-arithmetic
@@ -569,16 +580,16 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
         predicted = true;
         break;
       }
+      if (lean)   // prediction above the tolerance: measure after all, which needs the operand planes
+        HIP_TRY(launch_pack(ctx->R, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
     }
   }
 
-  HIP_TRY(launch_polar_finish(ctx->PX, ctx->M, h, blk, ctx->R, ctx->inner, s));
-  st = refresh_operand(ctx);
-  if (st != CONQUR_OK) return st;
+  // R = final iterate (unless it is there already), <R, M>, and the rotate operand planes of R^T: one pass
+  HIP_TRY(launch_polar_finish_pack(final_x, ctx->M, h, dh, ctx->np, final_x == ctx->R ? nullptr : ctx->R, ctx->RopT, plane,
+                                   ctx->dot_part, ctx->inner, s));
   // statistics restart empty (Alg. 1): M is overwritten by the next accumulate
-  HIP_TRY(launch_fill_zero(ctx->L, h * sizeof(double), s));
-  HIP_TRY(launch_fill_zero(ctx->rows, h * sizeof(unsigned long long), s));
-  HIP_TRY(launch_fill_zero(ctx->skipped, h * sizeof(unsigned long long), s));
+  HIP_TRY(launch_fill_zero(ctx->L, (size_t)3 * h * sizeof(double), s));
   if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
   ctx->ev_valid[ST_UPDATE] = timed;
   int nonfinite = 0;

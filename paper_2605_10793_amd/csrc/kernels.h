@@ -35,17 +35,20 @@ hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const
 // fro2[h] = sum M_h^2 (fro2 must be zero on entry).
 hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s);
 
-// X0 = (M + lambda*tau*R) / alpha with tau = ||M||_F/sqrt(dh), alpha = ||M||_F (1 + lambda);
-// a head with M = 0 starts from R itself.
-hipError_t launch_polar_start(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2,
-                              float* X, hipStream_t s);
+// Start of the polar iteration, fused with the operand packing: X0 = (M + lambda*tau*R) / alpha with
+// tau = ||M||_F/sqrt(dh), alpha = ||M||_F (1 + lambda) (a head with M = 0 starts from R itself), written as np bf16
+// split planes in natural (outN) and transposed (outT) layout and, if X32 is not null, in fp32.
+hipError_t launch_polar_start_pack(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, int np,
+                                   float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, hipStream_t s);
 
 // X += kappa * R over n elements (all heads).
 hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s);
 
-// R = X and inner[h] = <X_h, M_h> (inner must be zero on entry).
-hipError_t launch_polar_finish(const float* X, const float* M, int heads, int64_t n, float* R, double* inner,
-                               hipStream_t s);
+// End of the polar iteration, one pass over X: inner[h] = <X_h, M_h> (overwritten), the rotate operand outT =
+// np bf16 split planes of X^T, and, if R32 is not null, R32 = X.  dot_part: heads * pack_dot_partials(dh) doubles.
+int pack_dot_partials(int dh);
+hipError_t launch_polar_finish_pack(const float* X, const float* M, int heads, int dh, int np, float* R32, bf16_bits* outT,
+                                    int64_t plane, double* dot_part, double* inner, hipStream_t s);
 
 // Per-row symmetric fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse /
 // row_en, then their sums over rows: out[0] = SSE, out[1] = energy.

@@ -190,21 +190,61 @@ __global__ void __launch_bounds__(256) k_split_rows(const float* __restrict__ X,
 }
 
 // ---------------------------------------------------------------- fp32 matrix -> bf16 planes (natural / transposed)
-template <int NP>
+// One 64 x 64 tile per workgroup.  Optional fused work, so that the matrix is read once:
+//   START: the value packed is X0 = cm * src + cr * src2 (start of the polar iteration: src = M, src2 = R_prev,
+//          cm = 1/alpha, cr = lambda tau / alpha from fro2 = ||M||_F^2 of this batch entry);
+//   DOT:   also the partial sum over the tile of value * dotwith (the inner product <X, M>), one per workgroup;
+//   out32: also the value itself in fp32.
+struct PackFused {
+  const float* src2;      // START
+  const double* fro2;     // START
+  float lambda;           // START
+  int dh;                 // START (tau = ||M||_F / sqrt(dh))
+  const float* dotwith;   // DOT
+  double* dot_part;       // DOT: [batch][gridDim.y * gridDim.x]
+  float* out32;           // may be null
+};
+
+template <int NP, bool START, bool DOT>
 __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int rows, int cols, bf16_bits* __restrict__ outN,
-                                              bf16_bits* __restrict__ outT, int64_t plane) {
+                                              bf16_bits* __restrict__ outT, int64_t plane, const PackFused fx) {
   __shared__ float tile[64][65];
+  __shared__ double sh[4];
   const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
   const int64_t boff = (int64_t)blockIdx.z * rows * cols;
   const int t = threadIdx.x;
+  float cm = 1.0f, cr = 0.0f;
+  if constexpr (START) {
+    const double f = sqrt(fx.fro2[blockIdx.z]);
+    const bool empty = !(f > 0.0);
+    // lambda = 0 is taken as the limit lambda -> 0+ at fp32 resolution: the floor ties the
+    // update to R_prev on the null space of M (where every completion is optimal) and
+    // breaks exact degeneracies (repeated columns of M) that the iteration would preserve.
+    const float lambda = fmaxf(fx.lambda, 9.5367431640625e-07f);
+    const float tau = (float)(f / sqrt((double)fx.dh));
+    const float inv_alpha = empty ? 1.0f : (float)(1.0 / (f * (1.0 + (double)lambda)));
+    cm = empty ? 0.0f : inv_alpha;
+    cr = empty ? 1.0f : lambda * tau * inv_alpha;
+  }
+  double dot = 0.0;
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const int r = (t >> 4) + pass * 16;
     const int c = (t & 15) * 4;
     float f[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (r0 + r < rows && c0 + c < cols) {
-      const float4 v = *reinterpret_cast<const float4*>(src + boff + (int64_t)(r0 + r) * cols + c0 + c);
+      const int64_t off = boff + (int64_t)(r0 + r) * cols + c0 + c;
+      const float4 v = *reinterpret_cast<const float4*>(src + off);
       f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+      if constexpr (START) {
+        const float4 w = *reinterpret_cast<const float4*>(fx.src2 + off);
+        f[0] = cm * f[0] + cr * w.x; f[1] = cm * f[1] + cr * w.y; f[2] = cm * f[2] + cr * w.z; f[3] = cm * f[3] + cr * w.w;
+      }
+      if constexpr (DOT) {
+        const float4 m = *reinterpret_cast<const float4*>(fx.dotwith + off);
+        dot += (double)f[0] * m.x + (double)f[1] * m.y + (double)f[2] * m.z + (double)f[3] * m.w;
+      }
+      if (fx.out32) *reinterpret_cast<float4*>(fx.out32 + off) = make_float4(f[0], f[1], f[2], f[3]);
       if (outN) {
         bf16_bits p[4][NP];
 #pragma unroll
@@ -214,12 +254,16 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
           uint2 o;
           o.x = p[0][q] | ((uint32_t)p[1][q] << 16);
           o.y = p[2][q] | ((uint32_t)p[3][q] << 16);
-          *reinterpret_cast<uint2*>(outN + q * plane + boff + (int64_t)(r0 + r) * cols + c0 + c) = o;
+          *reinterpret_cast<uint2*>(outN + q * plane + off) = o;
         }
       }
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) tile[r][c + e] = f[e];
+  }
+  if constexpr (DOT) {
+    dot = block_sum_d(dot, sh);
+    if (t == 0) fx.dot_part[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x] = dot;
   }
   if (!outT) return;
   __syncthreads();
@@ -292,28 +336,6 @@ __global__ void __launch_bounds__(256) k_fro2(const float* __restrict__ M, int64
   if (threadIdx.x == 0) atomicAdd(fro2 + blockIdx.y, acc);
 }
 
-__global__ void __launch_bounds__(256) k_polar_start(const float* __restrict__ M, const float* __restrict__ R, int64_t n, int dh,
-                                                     float lambda, const double* __restrict__ fro2, float* __restrict__ X) {
-  const int h = blockIdx.y;
-  const double f = sqrt(fro2[h]);
-  const bool empty = !(f > 0.0);
-  // lambda = 0 is taken as the limit lambda -> 0+ at fp32 resolution: the floor ties the
-  // update to R_prev on the null space of M (where every completion is optimal) and
-  // breaks exact degeneracies (repeated columns of M) that the iteration would preserve.
-  lambda = fmaxf(lambda, 9.5367431640625e-07f);
-  const float tau = (float)(f / sqrt((double)dh));
-  const float inv_alpha = empty ? 1.0f : (float)(1.0 / (f * (1.0 + (double)lambda)));
-  const float cm = empty ? 0.0f : inv_alpha;
-  const float cr = empty ? 1.0f : lambda * tau * inv_alpha;
-  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
-    const float4 m = *reinterpret_cast<const float4*>(M + h * n + i);
-    const float4 r = *reinterpret_cast<const float4*>(R + h * n + i);
-    float4 o;
-    o.x = cm * m.x + cr * r.x; o.y = cm * m.y + cr * r.y; o.z = cm * m.z + cr * r.z; o.w = cm * m.w + cr * r.w;
-    *reinterpret_cast<float4*>(X + h * n + i) = o;
-  }
-}
-
 __global__ void __launch_bounds__(256) k_axpy(float* __restrict__ X, const float* __restrict__ R, int64_t n, float kappa) {
   for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
     float4 x = *reinterpret_cast<float4*>(X + i);
@@ -321,21 +343,6 @@ __global__ void __launch_bounds__(256) k_axpy(float* __restrict__ X, const float
     x.x += kappa * r.x; x.y += kappa * r.y; x.z += kappa * r.z; x.w += kappa * r.w;
     *reinterpret_cast<float4*>(X + i) = x;
   }
-}
-
-__global__ void __launch_bounds__(256) k_polar_finish(const float* __restrict__ X, const float* __restrict__ M, int64_t n,
-                                                      float* __restrict__ R, double* __restrict__ inner) {
-  __shared__ double sh[4];
-  const int h = blockIdx.y;
-  double acc = 0.0;
-  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
-    const float4 x = *reinterpret_cast<const float4*>(X + h * n + i);
-    const float4 m = *reinterpret_cast<const float4*>(M + h * n + i);
-    acc += (double)x.x * m.x + (double)x.y * m.y + (double)x.z * m.z + (double)x.w * m.w;
-    *reinterpret_cast<float4*>(R + h * n + i) = x;
-  }
-  acc = block_sum_d(acc, sh);
-  if (threadIdx.x == 0) atomicAdd(inner + h, acc);
 }
 
 // ---------------------------------------------------------------- fake-quantisation error
@@ -488,16 +495,41 @@ hipError_t launch_split_rows(const float* X, int64_t T, int64_t stride, int d, b
   return hipGetLastError();
 }
 
-hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
-                       int64_t plane, hipStream_t s) {
+template <bool START, bool DOT>
+static hipError_t launch_pack_impl(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
+                                   int64_t plane, const PackFused& fx, hipStream_t s) {
   dim3 grid((cols + 63) / 64, (rows + 63) / 64, batch);
   switch (np) {
-    case 1: hipLaunchKernelGGL(k_pack<1>, grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane); break;
-    case 2: hipLaunchKernelGGL(k_pack<2>, grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane); break;
-    case 3: hipLaunchKernelGGL(k_pack<3>, grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane); break;
+    case 1: hipLaunchKernelGGL((k_pack<1, START, DOT>), grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane, fx); break;
+    case 2: hipLaunchKernelGGL((k_pack<2, START, DOT>), grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane, fx); break;
+    case 3: hipLaunchKernelGGL((k_pack<3, START, DOT>), grid, dim3(256), 0, s, src, rows, cols, outN, outT, plane, fx); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
+                       int64_t plane, hipStream_t s) {
+  PackFused fx{};
+  return launch_pack_impl<false, false>(src, batch, rows, cols, np, outN, outT, plane, fx, s);
+}
+
+hipError_t launch_polar_start_pack(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, int np,
+                                   float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, hipStream_t s) {
+  PackFused fx{};
+  fx.src2 = R; fx.fro2 = fro2; fx.lambda = lambda; fx.dh = dh; fx.out32 = X32;
+  return launch_pack_impl<true, false>(M, heads, dh, dh, np, outN, outT, plane, fx, s);
+}
+
+int pack_dot_partials(int dh) { return ((dh + 63) / 64) * ((dh + 63) / 64); }
+
+hipError_t launch_polar_finish_pack(const float* X, const float* M, int heads, int dh, int np, float* R32, bf16_bits* outT,
+                                    int64_t plane, double* dot_part, double* inner, hipStream_t s) {
+  PackFused fx{};
+  fx.dotwith = M; fx.dot_part = dot_part; fx.out32 = R32;
+  hipError_t e = launch_pack_impl<false, true>(X, heads, dh, dh, np, nullptr, outT, plane, fx, s);
+  if (e != hipSuccess) return e;
+  return launch_sum_partials(dot_part, pack_dot_partials(dh), heads, inner, s);
 }
 
 hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
@@ -512,20 +544,8 @@ hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipSt
   return hipGetLastError();
 }
 
-hipError_t launch_polar_start(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, float* X,
-                              hipStream_t s) {
-  const int64_t n = (int64_t)dh * dh;
-  hipLaunchKernelGGL(k_polar_start, dim3(grid_for(n / 4, 2048), heads), dim3(256), 0, s, M, R, n, dh, lambda, fro2, X);
-  return hipGetLastError();
-}
-
 hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s) {
   hipLaunchKernelGGL(k_axpy, dim3(grid_for(n / 4, 2048)), dim3(256), 0, s, X, R, n, kappa);
-  return hipGetLastError();
-}
-
-hipError_t launch_polar_finish(const float* X, const float* M, int heads, int64_t n, float* R, double* inner, hipStream_t s) {
-  hipLaunchKernelGGL(k_polar_finish, dim3(grid_for(n / 4, 1024), heads), dim3(256), 0, s, X, M, n, R, inner);
   return hipGetLastError();
 }
 
