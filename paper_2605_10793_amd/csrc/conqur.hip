@@ -517,9 +517,24 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   double res = 0.0;
   int last_slot = 0;
   const float* final_x = ctx->PX;   // where the final iterate lives (the lean closing step writes R directly)
+  const bool keep_sq = !ctx->cfg.polar_verify || trace;
+  bool finished = false;
+  auto enqueue_finish = [&]() -> conqur_status {
+    // R = final iterate (unless it is there already), <R, M>, and the rotate operand planes of R^T: one pass
+    HIP_TRY(launch_polar_finish_pack(final_x, ctx->M, h, dh, ctx->np, final_x == ctx->R ? nullptr : ctx->R, ctx->RopT, plane,
+                                     ctx->dot_part, ctx->inner, s));
+    // statistics restart empty (Alg. 1): M is overwritten by the next accumulate
+    HIP_TRY(launch_fill_zero(ctx->L, (size_t)3 * h * sizeof(double), s));
+    if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
+    return CONQUR_OK;
+  };
   while (true) {
     HIP_TRY(gram(kSeg6, 0.5f, -0.5f, 2, true));
     last_slot = slot++;
+    // The first check after a main phase practically always calls for the quintic step: enqueue its D^2 product
+    // before the host waits for the residual, so that the device keeps working through the round trip.
+    const bool spec_square = closing == 0;
+    if (spec_square) HIP_TRY(square_correction(keep_sq));
     st = read_resid(last_slot, &res);
     if (st != CONQUR_OK) return st;
     if (trace) std::fprintf(stderr, "[conqur] polar closing check: resid_F=%.6e (iters %u)\n", res, iters);
@@ -542,9 +557,9 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     }
     const bf16_bits* W = ctx->PW;
     const bool quintic = res <= 1e-2 * std::sqrt((double)dh);   // rms deviation of the singular values below 1e-2
-    const bool predict = quintic && (!ctx->cfg.polar_verify || trace);
+    const bool predict = quintic && keep_sq;
     if (quintic) {
-      HIP_TRY(square_correction(predict));
+      if (!spec_square) HIP_TRY(square_correction(keep_sq));
       W = ctx->PW2;
     }
     // lean: the step is expected to be the last one -- no operand planes for a further Gram / apply, and the
@@ -565,6 +580,11 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       // calibrated against the measured residual).
       HIP_TRY(cube_norm());
       const int cslot = slot++;
+      if (lean) {   // expected to be the end: the finishing kernels go in before the host waits for the norm
+        st = enqueue_finish();
+        if (st != CONQUR_OK) return st;
+        finished = true;
+      }
       double d3 = 0.0;
       st = read_resid(cslot, &d3);
       if (st != CONQUR_OK) return st;
@@ -580,17 +600,17 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
         predicted = true;
         break;
       }
-      if (lean)   // prediction above the tolerance: measure after all, which needs the operand planes
+      if (lean) {   // prediction above the tolerance: measure after all, which needs the operand planes
+        finished = false;
         HIP_TRY(launch_pack(ctx->R, h, dh, dh, 3, ctx->PXn[cur], ctx->PXt[cur], plane, s));
+      }
     }
   }
 
-  // R = final iterate (unless it is there already), <R, M>, and the rotate operand planes of R^T: one pass
-  HIP_TRY(launch_polar_finish_pack(final_x, ctx->M, h, dh, ctx->np, final_x == ctx->R ? nullptr : ctx->R, ctx->RopT, plane,
-                                   ctx->dot_part, ctx->inner, s));
-  // statistics restart empty (Alg. 1): M is overwritten by the next accumulate
-  HIP_TRY(launch_fill_zero(ctx->L, (size_t)3 * h * sizeof(double), s));
-  if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
+  if (!finished) {
+    st = enqueue_finish();
+    if (st != CONQUR_OK) return st;
+  }
   ctx->ev_valid[ST_UPDATE] = timed;
   int nonfinite = 0;
   std::vector<double> inner(h), fro2(h);
