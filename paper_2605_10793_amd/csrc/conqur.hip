@@ -367,13 +367,16 @@ conqur_status conqur_get_batch_stats(conqur_ctx* ctx, conqur_batch_stats* out) {
 // equal-ripple choice (f(l) = f(u), q^2 = (u^2 + u l + l^2)/3) grows small values
 // fastest, but for l << u it sends the LARGEST singular values to the bottom of the
 // range, where low-precision rounding then perturbs exactly the directions that
-// carry the Procrustes objective.  So q is kept >= u / 1.532, which bounds
-// f(u) >= 0.5: the leading directions never fall below half of the current maximum
-// (growth of small values 2.30 instead of 2.60 per step).  Scaled so that the image
-// of [l, u] is [1 - E, 1 + E]; returns E.  For l = u = 1: the Newton-Schulz step.
+// carry the Procrustes objective.  So q is kept >= u / 1.65, which bounds
+// f(u) >= 0.23: the leading directions never fall below a quarter of the current
+// maximum (growth of small values 2.48 instead of 2.60 per step; with the bound at
+// 1.532, f(u) >= 0.5, one more step was needed at d >= 2048 for an objective that was
+// no closer to the optimum, while the unbounded choice loses a factor 2-5 in the
+// objective's deficit).  Scaled so that the image of [l, u] is [1 - E, 1 + E];
+// returns E.  For l = u = 1: the Newton-Schulz step.
 static double step_cubic(double l, double u, double* a, double* b) {
   const double s = u * u + u * l + l * l;
-  const double t = std::min(u * std::sqrt(3.0 / s), 1.532);
+  const double t = std::min(u * std::sqrt(3.0 / s), 1.65);
   const double q = u / t;
   auto f = [q](double x) { return 1.5 * (x / q) - 0.5 * (x / q) * (x / q) * (x / q); };
   const double lo = std::min(f(l), f(u));
