@@ -34,26 +34,28 @@ MEASURED_TRAFFIC_BYTES = {"c3": 3.21e8}
 
 
 def cpu_baseline(w, X0, R0, sample_tokens):
-    """The oracle, as it stands, on a bounded sample: one step_batch on `sample_tokens` rows of a c3 batch."""
+    """The oracle, as it stands, on a bounded sample: one step_batch on `sample_tokens` rows of a batch, and one Procrustes
+    at a width its Jacobi SVD finishes in seconds (extrapolated by its O(d^3) cost per sweep when that is below dh)."""
     from oracle import oracle as O
+    import numpy as np
     oc = O.OracleCalibrator(w.d, w.heads, w.dtype, R0, w.prox_lambda)
     Xs = X0[:sample_tokens]
     t0 = time.perf_counter()
     oc.step_batch(Xs)
     dt = time.perf_counter() - t0
-    # Procrustes: the Jacobi SVD is O(d^3) per sweep; time it at d = 384 and scale by (4096/384)^3
-    import numpy as np
-    ds = 1024
+    ds = min(w.dh, 2048)
     A = np.random.Generator(np.random.Philox(key=1)).standard_normal((ds, ds))
     t1 = time.perf_counter()
     O.procrustes(A)
     dp = time.perf_counter() - t1
+    scale = (w.dh / ds) ** 3 * w.heads
+    how = (f"timed at d={ds}: {dp:.2f} s, x ({w.dh}/{ds})^3 = {dp * scale:.0f} s extrapolated" if ds < w.dh else
+           f"at d={ds}: {dp:.2f} s per head, x {w.heads} heads = {dp * scale:.2f} s")
     return {
-        "value": sample_tokens / dt, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
-        "sample": f"oracle step_batch (rotate+corner+accumulate, fp64 naive loops) on the first {sample_tokens} "
-                  f"tokens of batch 0 of c3 (d={w.d}), {dt:.2f} s; oracle Procrustes (one-sided Jacobi SVD) "
-                  f"timed at d={ds}: {dp:.2f} s, x (4096/{ds})^3 = {dp * (4096 / ds) ** 3:.0f} s extrapolated",
-        "procrustes_s_extrapolated_d4096": dp * (4096 / ds) ** 3,
+        "value": len(Xs) / dt, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+        "sample": f"oracle step_batch (rotate+corner+accumulate, fp64 naive loops) on the first {len(Xs)} tokens of "
+                  f"batch 0 of {w.name} (d={w.d}, heads={w.heads}), {dt:.2f} s; oracle Procrustes (one-sided Jacobi SVD) {how}",
+        "procrustes_s": dp * scale,
     }
 
 
@@ -64,7 +66,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = one whole batch")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (the known-size kernel that scales "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -183,7 +185,7 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, host[0], R0, args.cpu_sample_tokens)
+        out["cpu_baseline"] = cpu_baseline(w, host[0], R0, args.cpu_sample_tokens or T)
     cal.close()
     print(json.dumps(out))
 
