@@ -149,9 +149,20 @@ conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, ui
 conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float* M_host);
 
 /*
+ * Keep (enable != 0) or drop (0, the default) the corner signs of every later
+ * conqur_step_batch for conqur_get_last_corners.  Only the fused per-head step
+ * (heads of width 128, bf16 activations) honours the switch -- there the signs never
+ * leave the compute unit otherwise and storing them doubles the step's HBM traffic;
+ * the general path produces them anyway as an operand of the accumulate GEMM.
+ */
+conqur_status conqur_set_taps(conqur_ctx* ctx, int enable);
+
+/*
  * Debug / parity taps of the last conqur_step_batch: the corner signs as int8
  * (+1 / -1; HOST, T*d, row-major like X) and the per-row norms (HOST, heads*T,
  * head-major; 0 marks a skipped row).  Either may be NULL.  Synchronises.
+ * CONQUR_ESTATE if the signs are asked for and the last step did not keep them
+ * (see conqur_set_taps).
  */
 conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs_host, float* norms_host);
 

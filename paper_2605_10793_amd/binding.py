@@ -23,7 +23,7 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
     "conqur_quant_error", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
-    "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
+    "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
 
@@ -77,6 +77,8 @@ def load() -> ctypes.CDLL:
         L.conqur_set_state.argtypes = [vp, vp, vp]
         L.conqur_get_last_corners.restype = i32
         L.conqur_get_last_corners.argtypes = [vp, vp, vp]
+        L.conqur_set_taps.restype = i32
+        L.conqur_set_taps.argtypes = [vp, i32]
         L.conqur_set_timing.restype = i32
         L.conqur_set_timing.argtypes = [vp, i32]
         L.conqur_get_timing.restype = i32
@@ -186,6 +188,10 @@ class Calibrator:
         nrm = np.empty((self.heads, T), dtype=np.float32)
         self._check(self._lib.conqur_get_last_corners(self._h, _np_ptr(S), _np_ptr(nrm)))
         return S, nrm
+
+    def set_taps(self, enable: bool) -> None:
+        """Keep the corner signs of later steps for last_corners() (only the fused per-head step drops them by default)."""
+        self._check(self._lib.conqur_set_taps(self._h, int(enable)))
 
     def set_timing(self, level) -> None:
         """0 off, 1 (or True) whole-call events, 2 per-stage events and GEMM clock probes as well."""

@@ -74,6 +74,12 @@ struct conqur_ctx {
   double *fro2 = nullptr, *inner = nullptr;          // [heads]
   double* dot_part = nullptr;                        // [heads][(dh/64)^2] per-tile partials of <R, M>
   int64_t last_T = 0;
+  // heads of width 128 with bf16 activations take the fused step kernel (head_step.hip)
+  bool head_fused = false;
+  float* Mpart = nullptr;                            // [head_splits][heads][128][128] partial M of the token shares
+  int head_splits = 0;
+  bool taps = false;                                 // keep the corner signs of every step for conqur_get_last_corners
+  bool last_signs_valid = false;
 
   int timing = 0;   // 0 off, 1 whole-call events, 2 per-stage events and GEMM clock probes as well
   unsigned long long* clk[2] = {nullptr, nullptr};   // clock probes of the step's rotate / accumulate GEMM
@@ -231,6 +237,11 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   A(dev_alloc(ctx, &ctx->resid, (size_t)kResidSlots * ctx->heads));
   ctx->resid_parts = gemm_num_partials((int)dh, (int)dh, ctx->heads);
   A(dev_alloc(ctx, &ctx->resid_part, (size_t)ctx->resid_parts * ctx->heads));
+  ctx->head_fused = ctx->dh == 128 && !ctx->f32;
+  if (ctx->head_fused) {
+    ctx->head_splits = head_step_splits(ctx->heads, ctx->tmax);
+    A(dev_alloc(ctx, &ctx->Mpart, (size_t)ctx->head_splits * blk));
+  }
   A(dev_alloc(ctx, &ctx->dot_part, (size_t)ctx->heads * pack_dot_partials(ctx->dh)));
   A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
   A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
@@ -255,6 +266,12 @@ conqur_status conqur_set_timing(conqur_ctx* ctx, int enable) {
   ctx->timing = enable;
   for (int s = 0; s < ST_COUNT; ++s) ctx->ev_valid[s] = false;
   ctx->clk_wg[0] = ctx->clk_wg[1] = 0;
+  return CONQUR_OK;
+}
+
+conqur_status conqur_set_taps(conqur_ctx* ctx, int enable) {
+  if (!ctx) return CONQUR_EINVAL;
+  ctx->taps = enable != 0;
   return CONQUR_OK;
 }
 
@@ -296,6 +313,26 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
   const int64_t Tk = round_up(T, 64);
   hipStream_t s = ctx->stream;
   StageTimer whole(ctx, ST_STEP, 1);   // ends when the function returns
+  if (ctx->head_fused) {
+    const int nsplit = std::min(ctx->head_splits, head_step_splits(ctx->heads, T));
+    {
+      StageTimer tm(ctx, ST_ROTATE);   // the fused kernel: rotate + normalise + corner + accumulate
+      HIP_TRY(launch_head_step128(reinterpret_cast<const bf16_bits*>(X), T, stride, ctx->heads, ctx->RopT, ctx->Mpart, nsplit,
+                                  ctx->nrm, ctx->tmax, ctx->L, ctx->rows, ctx->skipped, ctx->nonfinite,
+                                  ctx->taps ? ctx->St : nullptr, ctx->pitch, s));
+    }
+    {
+      StageTimer tm(ctx, ST_ACCUM);    // the token shares' partial M, summed in a fixed order
+      HIP_TRY(launch_head_reduce(ctx->Mpart, nsplit, ctx->heads, ctx->M, ctx->m_empty ? 0 : 1, s));
+    }
+    ctx->clk_wg[0] = ctx->clk_wg[1] = 0;
+    ctx->last_signs_valid = ctx->taps;
+    ctx->m_empty = false;
+    ctx->have_rows = true;
+    ctx->last_T = T;
+    return CONQUR_OK;
+  }
+  ctx->last_signs_valid = true;
   {
     StageTimer tm(ctx, ST_PREP);
     HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, s));
@@ -708,6 +745,8 @@ conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float
 conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs, float* norms) {
   if (!ctx) return CONQUR_EINVAL;
   if (ctx->last_T == 0) return fail(ctx, CONQUR_ESTATE, "no step_batch yet");
+  if (signs && !ctx->last_signs_valid)
+    return fail(ctx, CONQUR_ESTATE, "the last step did not keep the corner signs: call conqur_set_taps(ctx, 1) before it");
   const int64_t T = ctx->last_T, d = ctx->d, pitch = ctx->pitch;
   hipStream_t s = ctx->stream;
   std::vector<float> nrm((size_t)ctx->heads * T);

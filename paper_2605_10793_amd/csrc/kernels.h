@@ -50,6 +50,16 @@ int pack_dot_partials(int dh);
 hipError_t launch_polar_finish_pack(const float* X, const float* M, int heads, int dh, int np, float* R32, bf16_bits* outT,
                                     int64_t plane, double* dot_part, double* inner, hipStream_t s);
 
+// Fused statistics step for heads of width 128 with bf16 activations (head_step.hip): one kernel rotates, normalises,
+// takes the corners and accumulates; every workgroup (head, share of the tokens) stores a partial M_h into
+// Mpart [nsplit][heads][128][128], adds its share of L / rows / skipped, writes the row norms and, if St is not null,
+// the corner signs (+-1 as fp16, transposed [heads*128][pitch]).  launch_head_reduce then sets or adds the shares to M.
+int head_step_splits(int heads, int64_t T);
+hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, int heads, const bf16_bits* RopT, float* Mpart,
+                               int nsplit, float* nrm, int64_t ldn, double* L, unsigned long long* rows,
+                               unsigned long long* skipped, int* nonfinite, bf16_bits* St, int64_t pitch, hipStream_t s);
+hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, hipStream_t s);
+
 // Per-row symmetric fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse /
 // row_en, then their sums over rows: out[0] = SSE, out[1] = energy.
 hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,

@@ -43,6 +43,7 @@ def compare_step(B, cal, oc, X, w, tag):
     M_before = oc.M.copy()
     Y, S = oc.step_batch(X, True, True)
     Xd = B.to_device(X, w.dtype)
+    cal.set_taps(True)      # the fused per-head step keeps its corner signs only on request
     cal.step_batch(Xd)
     _, Mg, _ = cal.get_state(want_R=False)
     Sg, nrm = cal.last_corners(X.shape[0])
@@ -183,6 +184,43 @@ def test_polar_precision_improves_R(B):
             cal.close()
     assert errs[1] <= 0.5 * errs[0] and errs[2] <= errs[1] * 1.05
     assert errs[2] <= 1e-4
+
+
+@pytest.mark.parametrize("heads,T", [(1, 64), (2, 1), (3, 191), (32, 2048), (5, 777)])
+def test_fused_head_step_shapes(B, heads, T):
+    """The fused step kernel for heads of width 128: one tile, a single token, ragged tails, c4's full shape, a head
+    count that does not divide the chip; with and without the sign tap (the same kernel, only the store differs)."""
+    w = I.small_workload(128 * heads, T, n_batches=1, heads=heads, seed=300 + heads, massive_frac=0.01)
+    R0 = I.initial_rotation(w)
+    X = I.batch(w, 0, T)
+    if T > 8:
+        X[5] = 0.0
+    oc = O.OracleCalibrator(w.d, heads, "bf16", R0)
+    cal = B.Calibrator(w.d, heads, "bf16", R0, max_tokens=T)
+    try:
+        compare_step(B, cal, oc, X, w, f"fused h={heads} T={T}")
+        _, M1, _ = cal.get_state(want_R=False)
+        st1 = cal.batch_stats()
+        # a second context without the tap: identical M and statistics, and the tap reports that it has nothing
+        cal2 = B.Calibrator(w.d, heads, "bf16", R0, max_tokens=T)
+        try:
+            cal2.step_batch(B.to_device(X, "bf16"))
+            _, M2, _ = cal2.get_state(want_R=False)
+            assert np.array_equal(M1, M2)
+            st2 = cal2.batch_stats()
+            assert [s["rows"] for s in st1] == [s["rows"] for s in st2]
+            assert np.allclose([s["l1"] for s in st1], [s["l1"] for s in st2], rtol=1e-12)
+            with pytest.raises(B.ConqurError) as e:
+                cal2.last_corners(T)
+            assert e.value.status == B.ESTATE
+            # accumulate a second batch on top (read-modify-write of M by the reduce kernel)
+            cal2.step_batch(B.to_device(X, "bf16"))
+            _, M3, _ = cal2.get_state(want_R=False)
+            assert np.abs(M3 - 2.0 * M2).max() <= 1e-5 * np.abs(M2).max()
+        finally:
+            cal2.close()
+    finally:
+        cal.close()
 
 
 def test_c4_heads_reduced_tokens(B):
