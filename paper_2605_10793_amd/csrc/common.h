@@ -11,12 +11,19 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short bf16_bits;  // raw bf16 storage
 
-// fp32 -> bf16, round to nearest even (finite inputs; NaN stays NaN, Inf stays Inf).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// fp32 -> bf16, round to nearest even (NaN stays NaN, Inf stays Inf): the hardware conversion
+// (v_cvt_pk_bf16_f32, one instruction for two values).
 __device__ __forceinline__ bf16_bits f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_bits)((u >> 16) | 0x40);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_bits)(u >> 16);
+  const __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(unsigned short, b);
+}
+// Two values at once, packed lo | hi << 16.
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 __device__ __forceinline__ bf16_bits f32_to_f16(float f) {
   const _Float16 h = (_Float16)f;  // round to nearest even

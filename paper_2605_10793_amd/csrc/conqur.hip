@@ -526,6 +526,26 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     if (!planes_ready) HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s));
     const double e_stop = np_main == 1 ? 4e-3 : 5e-4;   // the safety margins below floor the ripple near 2e-4
     double l = l0, u = 1.0;
+    if (dh == 128 && np_main == 1 && iters < cap && !std::getenv("CONQUR_NO_FUSED_POLAR")) {
+      // heads of width 128: the whole schedule in one launch, the iterate stays in LDS (head_polar.hip)
+      PolarSchedule sc;
+      sc.nsteps = 0;
+      while (sc.nsteps < kPolarScheduleMax) {
+        double a, b;
+        const double E = step_cubic(l, u, &a, &b);
+        sc.a[sc.nsteps] = (float)a;
+        sc.b[sc.nsteps] = (float)b;
+        ++sc.nsteps;
+        if (E <= e_stop || iters + sc.nsteps >= cap) break;
+        l = 0.98 * (1.0 - E);
+        u = 1.01 * (1.0 + E);
+      }
+      HIP_TRY(launch_head_polar128(ctx->PXn[cur], ctx->PXt[cur], h, sc, ctx->PX, ctx->PXn[cur ^ 1], ctx->PXt[cur ^ 1], plane, s));
+      cur ^= 1;
+      iters += sc.nsteps;
+      if (trace) std::fprintf(stderr, "[conqur] polar main phase: %d steps in one launch, l0=%.3e\n", sc.nsteps, l0);
+      return CONQUR_OK;
+    }
     for (int k = 0; k < 64 && iters < cap && slot < kResidSlots - 8; ++k) {
       double a, b;
       const double E = step_cubic(l, u, &a, &b);

@@ -430,19 +430,17 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           }
           const int np_max = g.np_out > g.np_out_n ? g.np_out : g.np_out_n;
           for (int p = 0; p < np_max; ++p) {
-            bf16_bits hb[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              hb[r] = f32_to_bf16(v[r]);
-              v[r] -= bf16_to_f32(hb[r]);
-              if (p < g.np_out_n) g.Pn[p * g.plane_out + boff + (int64_t)(mb + r) * g.ldc + n] = hb[r];
+            uint2 t;   // the 4 values as bf16, packed; the remainder goes on to the next plane
+            t.x = f32x2_to_bf16x2(v[0], v[1]);
+            t.y = f32x2_to_bf16x2(v[2], v[3]);
+            v[0] -= __uint_as_float(t.x << 16); v[1] -= __uint_as_float(t.x & 0xffff0000u);
+            v[2] -= __uint_as_float(t.y << 16); v[3] -= __uint_as_float(t.y & 0xffff0000u);
+            if (p < g.np_out_n) {
+              bf16_bits* q = g.Pn + p * g.plane_out + boff + (int64_t)mb * g.ldc + n;
+              q[0] = (bf16_bits)t.x; q[g.ldc] = (bf16_bits)(t.x >> 16);
+              q[2 * g.ldc] = (bf16_bits)t.y; q[3 * g.ldc] = (bf16_bits)(t.y >> 16);
             }
-            if (p < g.np_out) {
-              uint2 t;
-              t.x = hb[0] | ((uint32_t)hb[1] << 16);
-              t.y = hb[2] | ((uint32_t)hb[3] << 16);
-              *reinterpret_cast<uint2*>(g.Pt + p * g.plane_out + boff + (int64_t)n * g.ldc + mb) = t;
-            }
+            if (p < g.np_out) *reinterpret_cast<uint2*>(g.Pt + p * g.plane_out + boff + (int64_t)n * g.ldc + mb) = t;
           }
         }
       }

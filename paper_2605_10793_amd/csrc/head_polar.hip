@@ -1,0 +1,166 @@
+// Main phase of the polar iteration for heads of width 128, one launch for all steps
+// (the composed cubics X <- X (a_k I + b_k X^T X) of the Procrustes update, Sec. 3.3).
+//
+// At this width the iterate (32 KiB as bf16, natural and transposed), and the
+// polynomial factor W (32 KiB) live in the LDS of one compute unit, so a workgroup
+// per head runs the whole schedule without touching HBM between steps; the general
+// path needs two GEMM launches per step, which at 128 x 128 are launch latency only.
+// Per step, with every product a 32x32x16 bf16 MFMA on K-contiguous operands:
+//   G = X^T X            A = B = X^T                     -> W = a I + b G, bf16, to LDS
+//   X' = X W             A = X,  B = W (symmetric)       -> accumulators hold X'   : packed stores give X'^T
+//   X'^T = W X^T         A = W,  B = X                   -> accumulators hold X'^T : packed stores give X'
+// (an accumulator lane owns 4 consecutive rows of one column, i.e. 8 contiguous bytes of the
+// transposed matrix: computing the product in both orientations replaces the scattered
+// 2-byte stores a single orientation would need for its own layout).
+// The last step writes what the closing iterations read: the fp32 iterate, three
+// transposed and two natural bf16 split planes.
+#include "kernels.h"
+
+namespace conqur {
+
+namespace {
+
+constexpr int DH = 128;
+constexpr int ROWB = 256;   // bytes per LDS row (128 bf16), 16 chunks of 16 bytes, XOR swizzled
+constexpr int kSmemBytes = 3 * DH * ROWB;
+
+__device__ __forceinline__ int loff(int row, int chunk) { return row * ROWB + ((chunk ^ (row & 15)) << 4); }
+
+__global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restrict__ Xn0, const bf16_bits* __restrict__ Xt0,
+                                                       const PolarSchedule sched, float* __restrict__ X32,
+                                                       bf16_bits* __restrict__ Pn, bf16_bits* __restrict__ Pt, int64_t plane) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* const sXn = smem;                  // X   : row r, K = column
+  unsigned char* const sXt = smem + DH * ROWB;      // X^T : row c, K = row of X
+  unsigned char* const sW = smem + 2 * DH * ROWB;   // W   : symmetric
+  const int h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int wm = wave >> 1, wn = wave & 1;          // this wavefront's 64 x 64 block of every 128 x 128 product
+  const int64_t hoff = (int64_t)h * DH * DH;
+
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int idx = q * 256 + tid, row = idx >> 4, chunk = idx & 15;
+    *reinterpret_cast<uint4*>(sXn + loff(row, chunk)) = *reinterpret_cast<const uint4*>(Xn0 + hoff + row * DH + chunk * 8);
+    *reinterpret_cast<uint4*>(sXt + loff(row, chunk)) = *reinterpret_cast<const uint4*>(Xt0 + hoff + row * DH + chunk * 8);
+  }
+  __syncthreads();
+
+  auto frag = [&](const unsigned char* base, int row, int kk) {
+    return *reinterpret_cast<const bf16x8*>(base + loff(row, 2 * kk + half));
+  };
+  // acc[i][j] = sum_k A[rowA + 32 i + .][k] B[rowB + 32 j + .][k]
+  auto product = [&](const unsigned char* A, int rowA, const unsigned char* B, int rowB, f32x16 (&acc)[2][2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = frag(A, rowA + 32 * i + col, kk);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j] = frag(B, rowB + 32 * j + col, kk);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  };
+  // Element e = 4 jj + ii of acc[i][j]: row m = rowA + 32 i + 8 jj + 4 half + ii, column n = rowB + 32 j + col.
+  // Store the transposed matrix into an LDS operand: row n, K positions m .. m + 3 (8 bytes).
+  auto store_transposed = [&](unsigned char* dst, int rowA, int rowB, const f32x16 (&acc)[2][2], float ci, float cg) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = rowB + 32 * j + col;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int m0 = rowA + 32 * i + 8 * jj + 4 * half;
+          float v[4];
+#pragma unroll
+          for (int ii = 0; ii < 4; ++ii) v[ii] = cg * acc[i][j][4 * jj + ii] + ((m0 + ii == n) ? ci : 0.0f);
+          uint2 pk;
+          pk.x = f32x2_to_bf16x2(v[0], v[1]);
+          pk.y = f32x2_to_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(dst + loff(n, m0 >> 3) + (m0 & 7) * 2) = pk;
+        }
+      }
+  };
+
+  f32x16 acc[2][2], accT[2][2];
+  for (int k = 0; k < sched.nsteps; ++k) {
+    const bool last = k + 1 == sched.nsteps;
+    // G = X^T X;  W = a I + b G (G symmetric: storing the transpose stores W itself)
+    product(sXt, 64 * wm, sXt, 64 * wn, acc);
+    store_transposed(sW, 64 * wm, 64 * wn, acc, sched.a[k], sched.b[k]);
+    __syncthreads();
+    product(sXn, 64 * wm, sW, 64 * wn, acc);    // X'   [r][c]
+    product(sW, 64 * wm, sXn, 64 * wn, accT);   // X'^T [c][r]
+    if (last) break;
+    __syncthreads();                            // every wavefront has read the old iterate
+    store_transposed(sXt, 64 * wm, 64 * wn, acc, 0.0f, 1.0f);
+    store_transposed(sXn, 64 * wm, 64 * wn, accT, 0.0f, 1.0f);
+    __syncthreads();
+  }
+
+  // Hand-over to the closing iterations: fp32 X, 3 transposed planes (from X') and 2 natural planes (from X'^T).
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = 64 * wn + 32 * j + col;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int m0 = 64 * wm + 32 * i + 8 * jj + 4 * half;
+        float v[4], t[4];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+          v[ii] = acc[i][j][4 * jj + ii];
+          t[ii] = accT[i][j][4 * jj + ii];
+          X32[hoff + (int64_t)(m0 + ii) * DH + n] = v[ii];
+        }
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+          uint2 pk;
+          pk.x = f32x2_to_bf16x2(v[0], v[1]);
+          pk.y = f32x2_to_bf16x2(v[2], v[3]);
+          v[0] -= __uint_as_float(pk.x << 16); v[1] -= __uint_as_float(pk.x & 0xffff0000u);
+          v[2] -= __uint_as_float(pk.y << 16); v[3] -= __uint_as_float(pk.y & 0xffff0000u);
+          *reinterpret_cast<uint2*>(Pt + p * plane + hoff + (int64_t)n * DH + m0) = pk;   // X^T[c = n][r = m0 ..]
+        }
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          uint2 pk;
+          pk.x = f32x2_to_bf16x2(t[0], t[1]);
+          pk.y = f32x2_to_bf16x2(t[2], t[3]);
+          t[0] -= __uint_as_float(pk.x << 16); t[1] -= __uint_as_float(pk.x & 0xffff0000u);
+          t[2] -= __uint_as_float(pk.y << 16); t[3] -= __uint_as_float(pk.y & 0xffff0000u);
+          *reinterpret_cast<uint2*>(Pn + p * plane + hoff + (int64_t)n * DH + m0) = pk;   // accT: X[r = n][c = m0 ..]
+        }
+      }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
+                                bf16_bits* Pn, bf16_bits* Pt, int64_t plane, hipStream_t s) {
+  if (heads < 1 || sched.nsteps < 1 || sched.nsteps > kPolarScheduleMax) return hipErrorInvalidValue;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_polar128), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kSmemBytes);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(k_head_polar128, dim3(heads), dim3(256), kSmemBytes, s, Xn0, Xt0, sched, X32, Pn, Pt, plane);
+  return hipGetLastError();
+}
+
+}  // namespace conqur
