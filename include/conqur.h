@@ -87,6 +87,7 @@ typedef struct {
   double ms;            /* device time of this update in milliseconds (all heads together)          */
   uint32_t orth_measured; /* 1: orth_err was measured; 0: it is the estimate                          */
   uint32_t reserved;
+  double l1;            /* L of the rows this update consumed (as conqur_batch_stats.l1 just before it)   */
 } conqur_update_stats;
 
 /*

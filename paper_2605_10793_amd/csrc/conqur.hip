@@ -55,8 +55,10 @@ struct conqur_ctx {
   bf16_bits* St = nullptr;     // [d][pitch] corner signs +-1, transposed (fp16, or bf16 for fp32 input)
   bf16_bits* Xs = nullptr;     // fp32 activations only: [3][tmax][d] split planes of X
   float *nrm = nullptr, *w = nullptr;  // [heads][tmax]
-  float* Lpart = nullptr;      // [heads][slabs][tmax]
-  int slabs_max = 0;
+  unsigned long long* cnt = nullptr;   // [heads][kCountSlots][2] rows / skipped counters of the general path
+  double* ldot = nullptr;              // [heads] <R_op, M> (l1 term / sqrt(dh)) of the general path
+  double* dotrm_part = nullptr;        // scratch of launch_dot_rm
+  std::vector<double> l_base;          // l1 offsets from rotations replaced while statistics were pending
   double* L = nullptr;         // [heads]
   unsigned long long *rows = nullptr, *skipped = nullptr;
   int* nonfinite = nullptr;
@@ -74,6 +76,7 @@ struct conqur_ctx {
   double *fro2 = nullptr, *inner = nullptr;          // [heads]
   double* dot_part = nullptr;                        // [heads][(dh/64)^2] per-tile partials of <R, M>
   int64_t last_T = 0;
+  size_t stat_words = 0;
   // heads of width 128 with bf16 activations take the fused step kernel (head_step.hip)
   bool head_fused = false;
   float* Mpart = nullptr;                            // [head_splits][heads][128][128] partial M of the token shares
@@ -205,8 +208,6 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
 
   const size_t blk = (size_t)ctx->heads * dh * dh;
   const size_t d = ctx->d, tmax = ctx->tmax, pitch = ctx->pitch, np = ctx->np;
-  // the widest tile the rotate GEMM can pick is 64 columns per slab pair -> slabs <= 2*ceil(dh/64)
-  ctx->slabs_max = 2 * (int)((dh + 63) / 64);
   hipError_t e = hipSuccess;
   auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   A(dev_alloc(ctx, &ctx->R, blk));
@@ -217,11 +218,16 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   if (ctx->f32) A(dev_alloc(ctx, &ctx->Xs, 3 * tmax * d));
   A(dev_alloc(ctx, &ctx->nrm, (size_t)ctx->heads * tmax));
   A(dev_alloc(ctx, &ctx->w, (size_t)ctx->heads * tmax));
-  A(dev_alloc(ctx, &ctx->Lpart, (size_t)ctx->heads * ctx->slabs_max * tmax));
-  // L, rows, skipped share one allocation so that one fill clears the batch statistics
-  A(dev_alloc(ctx, &ctx->L, (size_t)3 * ctx->heads));
+  // L, rows, skipped (fused per-head step) and the slot counters (general path) share one allocation so that one
+  // fill clears the batch statistics
+  ctx->stat_words = (size_t)3 * ctx->heads + (size_t)2 * kCountSlots * ctx->heads;
+  A(dev_alloc(ctx, &ctx->L, ctx->stat_words));
   ctx->rows = reinterpret_cast<unsigned long long*>(ctx->L + ctx->heads);
   ctx->skipped = ctx->rows + ctx->heads;
+  ctx->cnt = ctx->skipped + ctx->heads;
+  A(dev_alloc(ctx, &ctx->ldot, (size_t)ctx->heads));
+  A(dev_alloc(ctx, &ctx->dotrm_part, (size_t)ctx->heads * dot_rm_partials((int64_t)dh * dh)));
+  ctx->l_base.assign(ctx->heads, 0.0);
   A(dev_alloc(ctx, &ctx->nonfinite, (size_t)4));
   A(dev_alloc(ctx, reinterpret_cast<char**>(&ctx->Y), tmax * d * (ctx->f32 ? 4 : 2)));
   A(dev_alloc(ctx, &ctx->row_sse, tmax));
@@ -335,13 +341,12 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
   ctx->last_signs_valid = true;
   {
     StageTimer tm(ctx, ST_PREP);
-    HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, s));
+    HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, ctx->cnt, s));
     HIP_TRY(launch_transpose_scale(X, ctx->f32, T, Tk, stride, ctx->d, ctx->dh, ctx->w, ctx->tmax, ctx->Xt, ctx->pitch,
                                    (int64_t)ctx->d * ctx->pitch, ctx->np, s));
     if (ctx->f32)
       HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
   }
-  int slabs = 0;
   {
     StageTimer tm(ctx, ST_ROTATE);
     GemmArgs g;
@@ -349,9 +354,6 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
     g.C = ctx->St; g.ldc = ctx->pitch; g.batchC = (int64_t)ctx->dh * ctx->pitch;
     g.st_rows_valid = ctx->pitch;
     g.sign_f16 = ctx->f32 ? 0 : 1;   // the accumulate GEMM runs in fp16 for bf16 activations
-    slabs = gemm_sign_slabs(g.M, g.N, ctx->heads);
-    if (slabs > ctx->slabs_max) return fail(ctx, CONQUR_EHIP, "internal: slab count exceeds workspace");
-    g.Lpart = ctx->Lpart; g.ldl = ctx->tmax;
     const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
     ctx->clk_wg[0] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
     g.clk = ctx->clk_wg[0] ? ctx->clk[0] : nullptr;
@@ -375,27 +377,49 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
     g.clk = ctx->clk_wg[1] ? ctx->clk[1] : nullptr;
     HIP_TRY(launch_gemm_nt(g, EPI_F32, ctx->heads, s));
   }
-  {
-    StageTimer tm(ctx, ST_STATS);
-    HIP_TRY(launch_reduce_stats(ctx->Lpart, slabs, ctx->tmax, ctx->nrm, ctx->tmax, T, ctx->heads, ctx->L, ctx->rows,
-                                ctx->skipped, s));
-  }
+  // no statistics kernel: the row counters were taken with the norms, and the l1 term of the accumulated rows is
+  // sqrt(dh) <R_op, M> (k_dot_rm), evaluated when asked for and at the start of the update.
   ctx->m_empty = false;
   ctx->have_rows = true;
   ctx->last_T = T;
   return CONQUR_OK;
 }
 
+// Host copy of the batch statistics; for the general path the l1 term is evaluated here from M (see k_dot_rm).
+static conqur_status read_stats(conqur_ctx* ctx, std::vector<double>* L, std::vector<unsigned long long>* rows,
+                                std::vector<unsigned long long>* skipped) {
+  const int h = ctx->heads;
+  hipStream_t s = ctx->stream;
+  std::vector<double> buf(ctx->stat_words);
+  std::vector<double> ldot(h, 0.0);
+  if (!ctx->head_fused && !ctx->m_empty) {
+    HIP_TRY(launch_dot_rm(ctx->R, ctx->M, h, (int64_t)ctx->dh * ctx->dh, ctx->f32 ? 0 : 1, ctx->dotrm_part, ctx->ldot, s));
+    HIP_TRY(hipMemcpyAsync(ldot.data(), ctx->ldot, h * sizeof(double), hipMemcpyDeviceToHost, s));
+  }
+  HIP_TRY(hipMemcpyAsync(buf.data(), ctx->L, ctx->stat_words * sizeof(double), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  const unsigned long long* u = reinterpret_cast<const unsigned long long*>(buf.data());
+  L->assign(h, 0.0); rows->assign(h, 0); skipped->assign(h, 0);
+  for (int i = 0; i < h; ++i) {
+    (*L)[i] = ctx->head_fused ? buf[i] : ctx->l_base[i] + std::sqrt((double)ctx->dh) * ldot[i];
+    (*rows)[i] = u[h + i];
+    (*skipped)[i] = u[2 * h + i];
+    for (int q = 0; q < kCountSlots; ++q) {
+      (*rows)[i] += u[3 * h + ((size_t)i * kCountSlots + q) * 2];
+      (*skipped)[i] += u[3 * h + ((size_t)i * kCountSlots + q) * 2 + 1];
+    }
+  }
+  return CONQUR_OK;
+}
+
 conqur_status conqur_get_batch_stats(conqur_ctx* ctx, conqur_batch_stats* out) {
   if (!ctx || !out) return CONQUR_EINVAL;
-  const int h = ctx->heads;
-  std::vector<double> L(h);
-  std::vector<unsigned long long> rows(h), skipped(h);
-  HIP_TRY(hipMemcpyAsync(L.data(), ctx->L, h * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
-  HIP_TRY(hipMemcpyAsync(rows.data(), ctx->rows, h * sizeof(unsigned long long), hipMemcpyDeviceToHost, ctx->stream));
-  HIP_TRY(hipMemcpyAsync(skipped.data(), ctx->skipped, h * sizeof(unsigned long long), hipMemcpyDeviceToHost, ctx->stream));
-  HIP_TRY(hipStreamSynchronize(ctx->stream));
-  for (int i = 0; i < h; ++i) { out[i].rows = rows[i]; out[i].skipped = skipped[i]; out[i].l1 = L[i]; }
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  std::vector<double> L;
+  std::vector<unsigned long long> rows, skipped;
+  const conqur_status st = read_stats(ctx, &L, &rows, &skipped);
+  if (st != CONQUR_OK) return st;
+  for (int i = 0; i < ctx->heads; ++i) { out[i].rows = rows[i]; out[i].skipped = skipped[i]; out[i].l1 = L[i]; }
   return CONQUR_OK;
 }
 
@@ -444,8 +468,12 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   int cur = 0;            // which ping-pong plane buffer holds the iterate
   // X0 = (M + lambda tau R) / alpha, alpha = ||M||_F (1 + lambda) >= ||X0||_2, written straight as the operand
   // planes of the first step (no fp32 copy: at least one main step runs, and the last one writes the fp32 iterate)
+  // The same pass evaluates the l1 term of the rows this update consumes (general path; the fused per-head step
+  // keeps it as it goes): a copy of either is taken here, before the statistics are cleared.
   HIP_TRY(launch_polar_start_pack(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, np_main, nullptr,
-                                  ctx->PXn[cur], ctx->PXt[cur], plane, s));
+                                  ctx->PXn[cur], ctx->PXt[cur], plane, ctx->f32 ? 0 : 1,
+                                  ctx->head_fused ? nullptr : ctx->dot_part, ctx->ldot, s));
+  if (ctx->head_fused) HIP_TRY(hipMemcpyAsync(ctx->ldot, ctx->L, h * sizeof(double), hipMemcpyDeviceToDevice, s));
   int slot = 0;           // next residual-history slot
   uint32_t iters = 0, closing = 0;
 
@@ -584,7 +612,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     HIP_TRY(launch_polar_finish_pack(final_x, ctx->M, h, dh, ctx->np, final_x == ctx->R ? nullptr : ctx->R, ctx->RopT, plane,
                                      ctx->dot_part, ctx->inner, s));
     // statistics restart empty (Alg. 1): M is overwritten by the next accumulate
-    HIP_TRY(launch_fill_zero(ctx->L, (size_t)3 * h * sizeof(double), s));
+    HIP_TRY(launch_fill_zero(ctx->L, ctx->stat_words * sizeof(double), s));
     if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
     return CONQUR_OK;
   };
@@ -673,7 +701,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   }
   ctx->ev_valid[ST_UPDATE] = timed;
   int nonfinite = 0;
-  std::vector<double> inner(h), fro2(h);
+  std::vector<double> inner(h), fro2(h), ldot(h);
+  HIP_TRY(hipMemcpyAsync(ldot.data(), ctx->ldot, h * sizeof(double), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipMemcpyAsync(inner.data(), ctx->inner, h * sizeof(double), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipMemcpyAsync(fro2.data(), ctx->fro2, h * sizeof(double), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipMemcpyAsync(&nonfinite, ctx->nonfinite, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -688,8 +717,10 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       out[q].iters = iters; out[q].accurate = closing; out[q].orth_measured = predicted ? 0u : 1u;
       out[q].orth_err = std::sqrt(hist[(size_t)last_slot * h + q]);
       out[q].inner = inner[q]; out[q].m_fro = std::sqrt(fro2[q]); out[q].ms = ms;
+      out[q].l1 = ctx->head_fused ? ldot[q] : ctx->l_base[q] + std::sqrt((double)dh) * ldot[q];
     }
   }
+  ctx->l_base.assign(h, 0.0);
   if (!converged) return fail(ctx, CONQUR_ENOCONV, "update_rotation: polar iteration hit polar_max_iters");
   if (nonfinite) return fail(ctx, CONQUR_ENONFINITE, "rows with non-finite values were skipped");
   return CONQUR_OK;
@@ -748,17 +779,36 @@ conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float
   if (!ctx) return CONQUR_EINVAL;
   const size_t blk = (size_t)ctx->heads * ctx->dh * ctx->dh;
   hipStream_t s = ctx->stream;
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int h = ctx->heads;
+  const int64_t n = (int64_t)ctx->dh * ctx->dh;
+  // The general path reads the l1 term of the pending rows off M through the current rotation (k_dot_rm).  Replacing
+  // the rotation while rows are pending keeps it right by moving the difference into an offset.
+  const bool rebase = R_host && !M_host && !ctx->head_fused && !ctx->m_empty;
+  std::vector<double> d_old(h, 0.0), d_new(h, 0.0);
+  if (rebase) {
+    HIP_TRY(launch_dot_rm(ctx->R, ctx->M, h, n, ctx->f32 ? 0 : 1, ctx->dotrm_part, ctx->ldot, s));
+    HIP_TRY(hipMemcpyAsync(d_old.data(), ctx->ldot, h * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+  }
   if (R_host) {
     HIP_TRY(hipMemcpyAsync(ctx->R, R_host, blk * sizeof(float), hipMemcpyHostToDevice, s));
     conqur_status st = refresh_operand(ctx);
     if (st != CONQUR_OK) return st;
   }
+  if (rebase) {
+    HIP_TRY(launch_dot_rm(ctx->R, ctx->M, h, n, ctx->f32 ? 0 : 1, ctx->dotrm_part, ctx->ldot, s));
+    HIP_TRY(hipMemcpyAsync(d_new.data(), ctx->ldot, h * sizeof(double), hipMemcpyDeviceToHost, s));
+  }
   if (M_host) {
     HIP_TRY(hipMemcpyAsync(ctx->M, M_host, blk * sizeof(float), hipMemcpyHostToDevice, s));
     ctx->m_empty = false;
     ctx->have_rows = true;
+    ctx->l_base.assign(h, 0.0);   // the rows behind the old M are gone
   }
   HIP_TRY(hipStreamSynchronize(s));
+  if (rebase)
+    for (int i = 0; i < h; ++i) ctx->l_base[i] += std::sqrt((double)ctx->dh) * (d_old[i] - d_new[i]);
   return CONQUR_OK;
 }
 

@@ -11,7 +11,7 @@
 namespace conqur {
 
 enum GemmEpilogue : int {
-  EPI_SIGN = 0,  // corner signs, transposed: St[n][m] = +-1 (bf16), and per-row sum_n |acc| partials
+  EPI_SIGN = 0,  // corner signs, transposed: St[n][m] = +-1 (bf16 or fp16)
   EPI_ACT = 1,   // Y[m][n] = acc, stored as bf16 or fp32 (rotated activations for the quantiser score)
   EPI_F32 = 2,   // C[m][n] = acc (+ C[m][n] if accumulate), fp32
   EPI_GRAMW = 3, // acc = Gram matrix G (A and B the same operand, so acc is symmetric): W = coef_i*I + coef_g*G
@@ -42,8 +42,6 @@ struct GemmArgs {
   int accumulate;          // EPI_F32: add to C instead of overwriting
   int64_t st_rows_valid;   // EPI_SIGN: St rows hold this many m entries (padded pitch), multiple of 4
   int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
-  float* Lpart;            // EPI_SIGN: [batch][slabs][ldl] partial sums of |acc| over the slab's columns
-  int64_t ldl;             //           slabs = 2 * tiles_n
   double* resid_part;      // EPI_GRAMW: [batch][gemm_num_partials()] per-wavefront sums of (acc - I)^2, or null.
                            // (No atomics: same-address atomics from all XCDs serialise at the memory side.)
   float coef_i, coef_g;    // EPI_GRAMW
@@ -71,8 +69,5 @@ int gemm_num_workgroups(int M, int N, int batch);
 // Per-batch-entry count of the partial sums the EPI_GRAMW epilogue writes for an M x N problem.
 int gemm_num_partials(int M, int N, int batch);
 
-// Number of column slabs the EPI_SIGN epilogue writes for an N-wide problem
-// (depends on the tile the launcher picks for (M, N, batch)).
-int gemm_sign_slabs(int M, int N, int batch);
 
 }  // namespace conqur

@@ -264,18 +264,13 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
 
   if constexpr (EPI == EPI_SIGN) {
     bf16_bits* St = reinterpret_cast<bf16_bits*>(g.C) + (int64_t)bz * g.batchC;
-    const int slabs = tiles_n * WGN;
     const uint32_t one = g.sign_f16 ? 0x3C00u : 0x3F80u;
-    float* Lp = g.Lpart + ((int64_t)bz * slabs + tn * WGN + wn) * g.ldl;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      float rs[16];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) rs[e] = 0.0f;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int n = nw + j * 32 + col;
-        const bool nok = n < g.N;
+        if (n >= g.N) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int mb = mw + i * 32 + 8 * q + 4 * half;
@@ -283,28 +278,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           uint2 v;  // +1 with the sign bit of each accumulator (sgn(+-0) = +1, so test >= 0)
           v.x = (a[4 * q + 0] >= 0.0f ? one : one | 0x8000u) | ((a[4 * q + 1] >= 0.0f ? one : one | 0x8000u) << 16);
           v.y = (a[4 * q + 2] >= 0.0f ? one : one | 0x8000u) | ((a[4 * q + 3] >= 0.0f ? one : one | 0x8000u) << 16);
-          if (nok && mb < g.st_rows_valid) *reinterpret_cast<uint2*>(St + (int64_t)n * g.ldc + mb) = v;
-          if (nok) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) rs[4 * q + r] += fabsf(a[4 * q + r]);
-          }
+          if (mb < g.st_rows_valid) *reinterpret_cast<uint2*>(St + (int64_t)n * g.ldc + mb) = v;
         }
       }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float v = rs[e];
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-        rs[e] = v;
-      }
-      if (col == 0) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m < g.M) Lp[m] = rs[e];
-        }
-      }
-    }
   } else if constexpr (EPI == EPI_ACT) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -541,11 +517,6 @@ int gemm_num_partials(int M, int N, int batch) {
 int gemm_num_workgroups(int M, int N, int batch) {
   const Tile& t = kTiles[pick_tile(M, N, batch)];
   return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
-}
-
-int gemm_sign_slabs(int M, int N, int batch) {
-  const Tile& t = kTiles[pick_tile(M, N, batch)];
-  return t.wgn * ((N + t.bn - 1) / t.bn);
 }
 
 hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStream_t stream) {

@@ -9,8 +9,10 @@ namespace conqur {
 
 // n_i = ||x_i||_2 over each head slice; w_i = 1/(n_i*sqrt(dh)), or 0 for a row that is
 // all zero or holds a non-finite value (then nrm = 0 and *nonfinite is raised for NaN/Inf).
+// cnt: [heads][kCountSlots][2] counters (rows that enter M, rows skipped), row i counts into slot i % kCountSlots.
+constexpr int kCountSlots = 64;
 hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh,
-                            float* nrm, float* w, int64_t ldn, int* nonfinite, hipStream_t s);
+                            float* nrm, float* w, int64_t ldn, int* nonfinite, unsigned long long* cnt, hipStream_t s);
 
 // Xt[p][k][i] = x_ik * w_{head(k), i} for i < T, 0 for T <= i < Tk.  np = 1 (bf16 activations):
 // one fp16 plane; np = 3 (fp32 activations): three bf16 split planes (exact).
@@ -27,10 +29,11 @@ hipError_t launch_split_rows(const float* X, int64_t T, int64_t stride, int d, b
 hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
                        int64_t plane, hipStream_t s);
 
-// L[h] += sum_i (sum_slab Lpart[h][slab][i]) / nrm[h][i]; rows/skipped counts.
-hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
-                               int heads, double* L, unsigned long long* rows, unsigned long long* skipped,
-                               hipStream_t s);
+// out[h] = <R_op,h , M_h> over n elements per head, R_op = R rounded to bf16 if round_bf16 else R (the l1 term of
+// the accumulated rows is sqrt(dh) times this).  part: heads * dot_rm_partials(n) doubles of scratch.
+int dot_rm_partials(int64_t n);
+hipError_t launch_dot_rm(const float* R, const float* M, int heads, int64_t n, int round_bf16, double* part, double* out,
+                         hipStream_t s);
 
 // fro2[h] = sum M_h^2 (fro2 must be zero on entry).
 hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s);
@@ -38,8 +41,11 @@ hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipSt
 // Start of the polar iteration, fused with the operand packing: X0 = (M + lambda*tau*R) / alpha with
 // tau = ||M||_F/sqrt(dh), alpha = ||M||_F (1 + lambda) (a head with M = 0 starts from R itself), written as np bf16
 // split planes in natural (outN) and transposed (outT) layout and, if X32 is not null, in fp32.
+// If dot_part is not null (heads * pack_dot_partials(dh) doubles), also dot_out[h] = <R_op,h , M_h> (R_op = R rounded to bf16 if
+// round_bf16), the quantity of launch_dot_rm, from the same pass.
 hipError_t launch_polar_start_pack(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, int np,
-                                   float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, hipStream_t s);
+                                   float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, int round_bf16,
+                                   double* dot_part, double* dot_out, hipStream_t s);
 
 // X += kappa * R over n elements (all heads).
 hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s);

@@ -40,7 +40,7 @@ __device__ __forceinline__ double block_sum_d(double v, double* sh) {
 template <bool F32>
 __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, int64_t T, int64_t stride, int heads, int dh,
                                                    float* __restrict__ nrm, float* __restrict__ w, int64_t ldn,
-                                                   int* __restrict__ nonfinite) {
+                                                   int* __restrict__ nonfinite, unsigned long long* __restrict__ cnt) {
   const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (gw >= T * heads) return;
@@ -91,6 +91,9 @@ __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, i
     }
     nrm[(int64_t)h * ldn + i] = n;
     w[(int64_t)h * ldn + i] = wi;
+    // rows that enter M / rows skipped, counted into one of kCountSlots slots per head so that the atomics of a
+    // batch spread over many addresses (atomics from all XCDs on one address serialise)
+    atomicAdd(cnt + ((int64_t)h * kCountSlots + (i % kCountSlots)) * 2 + (n > 0.0f ? 0 : 1), 1ull);
   }
 }
 
@@ -201,7 +204,8 @@ struct PackFused {
   float lambda;           // START
   int dh;                 // START (tau = ||M||_F / sqrt(dh))
   const float* dotwith;   // DOT
-  double* dot_part;       // DOT: [batch][gridDim.y * gridDim.x]
+  double* dot_part;       // DOT: [batch][gridDim.y * gridDim.x]; START: same for <R_op, M>, or null
+  int round_bf16;         // START: R_op is src2 rounded to bf16
   float* out32;           // may be null
 };
 
@@ -237,8 +241,16 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
       const float4 v = *reinterpret_cast<const float4*>(src + off);
       f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
       if constexpr (START) {
-        const float4 w = *reinterpret_cast<const float4*>(fx.src2 + off);
+        float4 w = *reinterpret_cast<const float4*>(fx.src2 + off);
+        const float m4[4] = {f[0], f[1], f[2], f[3]};
         f[0] = cm * f[0] + cr * w.x; f[1] = cm * f[1] + cr * w.y; f[2] = cm * f[2] + cr * w.z; f[3] = cm * f[3] + cr * w.w;
+        if (fx.dot_part) {   // <R_op, M> on the way (the l1 term of the rows this update consumes; see k_dot_rm)
+          if (fx.round_bf16) {
+            w.x = bf16_to_f32(f32_to_bf16(w.x)); w.y = bf16_to_f32(f32_to_bf16(w.y));
+            w.z = bf16_to_f32(f32_to_bf16(w.z)); w.w = bf16_to_f32(f32_to_bf16(w.w));
+          }
+          dot += (double)m4[0] * w.x + (double)m4[1] * w.y + (double)m4[2] * w.z + (double)m4[3] * w.w;
+        }
       }
       if constexpr (DOT) {
         const float4 m = *reinterpret_cast<const float4*>(fx.dotwith + off);
@@ -261,7 +273,7 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
 #pragma unroll
     for (int e = 0; e < 4; ++e) tile[r][c + e] = f[e];
   }
-  if constexpr (DOT) {
+  if (DOT || (START && fx.dot_part)) {
     dot = block_sum_d(dot, sh);
     if (t == 0) fx.dot_part[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x] = dot;
   }
@@ -286,42 +298,26 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
 }
 
 // ---------------------------------------------------------------- statistics
-// One block per 64 tokens of one head: thread (t & 63) owns a token, (t >> 6) a quarter
-// of the column slabs, so that the slab partials are read coalesced and in parallel.
-__global__ void __launch_bounds__(256) k_reduce_stats(const float* __restrict__ Lpart, int slabs, int64_t ldl,
-                                                      const float* __restrict__ nrm, int64_t ldn, int64_t T,
-                                                      double* __restrict__ L, unsigned long long* __restrict__ rows,
-                                                      unsigned long long* __restrict__ skipped) {
+// part[h][block] = sum over the block's elements of M_h * R_op,h, with R_op = R rounded to bf16 (bf16 activations) or R
+// itself.  The l1 term of the accumulated rows is sqrt(dh) <R_op, M>: sum_i ||y_i||_1 / ||x_i|| = sum_i sum_n
+// sgn(y_in) y_in / ||x_i|| with y_i = x_i R_op and M = sum_i (x_i/||x_i||)^T sgn(y_i)/sqrt(dh) (the l1 identity of
+// Sec. 3.2 per site), as long as every row was rotated with this R_op.
+__global__ void __launch_bounds__(256) k_dot_rm(const float* __restrict__ R, const float* __restrict__ M, int64_t n, int round_bf16,
+                                                double* __restrict__ part) {
   __shared__ double sh[4];
-  __shared__ float part[4][64];
-  const int h = blockIdx.y;
-  const int tok = threadIdx.x & 63, quarter = threadIdx.x >> 6;
-  const int64_t i = (int64_t)blockIdx.x * 64 + tok;
-  float s = 0.0f;
-  if (i < T) {
-    const float* p = Lpart + (int64_t)h * slabs * ldl + i;
-#pragma unroll 8
-    for (int q = quarter; q < slabs; q += 4) s += p[(int64_t)q * ldl];
-  }
-  part[quarter][tok] = s;
-  __syncthreads();
-  double acc = 0.0, cnt = 0.0, tot = 0.0;
-  if (quarter == 0 && i < T) {
-    tot = 1.0;
-    const float n = nrm[(int64_t)h * ldn + i];
-    if (n > 0.0f) {
-      acc = ((double)part[0][tok] + (double)part[1][tok] + (double)part[2][tok] + (double)part[3][tok]) / (double)n;
-      cnt = 1.0;
+  const int64_t hoff = (int64_t)blockIdx.y * n;
+  double acc = 0.0;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
+    float4 r = *reinterpret_cast<const float4*>(R + hoff + i);
+    const float4 m = *reinterpret_cast<const float4*>(M + hoff + i);
+    if (round_bf16) {
+      r.x = bf16_to_f32(f32_to_bf16(r.x)); r.y = bf16_to_f32(f32_to_bf16(r.y));
+      r.z = bf16_to_f32(f32_to_bf16(r.z)); r.w = bf16_to_f32(f32_to_bf16(r.w));
     }
+    acc += (double)r.x * m.x + (double)r.y * m.y + (double)r.z * m.z + (double)r.w * m.w;
   }
   acc = block_sum_d(acc, sh);
-  cnt = block_sum_d(cnt, sh);
-  tot = block_sum_d(tot, sh);
-  if (threadIdx.x == 0) {
-    atomicAdd(L + h, acc);
-    atomicAdd(rows + h, (unsigned long long)cnt);
-    atomicAdd(skipped + h, (unsigned long long)(tot - cnt));
-  }
+  if (threadIdx.x == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = acc;
 }
 
 __global__ void __launch_bounds__(256) k_fro2(const float* __restrict__ M, int64_t n, double* __restrict__ fro2) {
@@ -466,13 +462,13 @@ inline int grid_for(int64_t items, int cap = 4096) {
 }  // namespace
 
 hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh, float* nrm, float* w,
-                            int64_t ldn, int* nonfinite, hipStream_t s) {
+                            int64_t ldn, int* nonfinite, unsigned long long* cnt, hipStream_t s) {
   const int64_t waves = T * heads;
   dim3 grid((unsigned)((waves + 3) / 4));
   if (x_is_f32)
-    hipLaunchKernelGGL(k_row_norms<true>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite);
+    hipLaunchKernelGGL(k_row_norms<true>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite, cnt);
   else
-    hipLaunchKernelGGL(k_row_norms<false>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite);
+    hipLaunchKernelGGL(k_row_norms<false>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite, cnt);
   return hipGetLastError();
 }
 
@@ -514,14 +510,18 @@ hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, 
   return launch_pack_impl<false, false>(src, batch, rows, cols, np, outN, outT, plane, fx, s);
 }
 
+int pack_dot_partials(int dh) { return ((dh + 63) / 64) * ((dh + 63) / 64); }
+
 hipError_t launch_polar_start_pack(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, int np,
-                                   float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, hipStream_t s) {
+                                   float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, int round_bf16,
+                                   double* dot_part, double* dot_out, hipStream_t s) {
   PackFused fx{};
   fx.src2 = R; fx.fro2 = fro2; fx.lambda = lambda; fx.dh = dh; fx.out32 = X32;
-  return launch_pack_impl<true, false>(M, heads, dh, dh, np, outN, outT, plane, fx, s);
+  fx.dot_part = dot_part; fx.round_bf16 = round_bf16;
+  hipError_t e = launch_pack_impl<true, false>(M, heads, dh, dh, np, outN, outT, plane, fx, s);
+  if (e != hipSuccess || !dot_part) return e;
+  return launch_sum_partials(dot_part, pack_dot_partials(dh), heads, dot_out, s);
 }
-
-int pack_dot_partials(int dh) { return ((dh + 63) / 64) * ((dh + 63) / 64); }
 
 hipError_t launch_polar_finish_pack(const float* X, const float* M, int heads, int dh, int np, float* R32, bf16_bits* outT,
                                     int64_t plane, double* dot_part, double* inner, hipStream_t s) {
@@ -532,11 +532,15 @@ hipError_t launch_polar_finish_pack(const float* X, const float* M, int heads, i
   return launch_sum_partials(dot_part, pack_dot_partials(dh), heads, inner, s);
 }
 
-hipError_t launch_reduce_stats(const float* Lpart, int slabs, int64_t ldl, const float* nrm, int64_t ldn, int64_t T,
-                               int heads, double* L, unsigned long long* rows, unsigned long long* skipped, hipStream_t s) {
-  hipLaunchKernelGGL(k_reduce_stats, dim3((unsigned)((T + 63) / 64), heads), dim3(256), 0, s, Lpart, slabs, ldl, nrm, ldn, T, L, rows,
-                     skipped);
-  return hipGetLastError();
+int dot_rm_partials(int64_t n) { return grid_for(n / 4, 1024); }
+
+hipError_t launch_dot_rm(const float* R, const float* M, int heads, int64_t n, int round_bf16, double* part, double* out,
+                         hipStream_t s) {
+  const int blocks = dot_rm_partials(n);
+  hipLaunchKernelGGL(k_dot_rm, dim3(blocks, heads), dim3(256), 0, s, R, M, n, round_bf16, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_sum_partials(part, blocks, heads, out, s);
 }
 
 hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s) {

@@ -76,8 +76,11 @@ def compare_update(B, cal, oc, w, tag, check_R):
     M = oc.M.copy()
     R_prev = oc.R.copy()
     cal.set_state(R=R_prev, M=M.astype(np.float32))
+    L_before = np.array(oc.L, dtype=np.float64).copy()
     st_o = oc.update_rotation()
     rc, st_g = cal.update_rotation(allow=(B.ENONFINITE,))
+    for h in range(w.heads):     # the l1 term of the rows this update consumed
+        assert abs(st_g[h]["l1"] - L_before[h]) <= TOL_REL * abs(L_before[h]) + 1e-12, (tag, h, st_g[h]["l1"], L_before[h])
     Rg, _, _ = cal.get_state(want_M=False)
     for h in range(w.heads):
         R64 = Rg[h].astype(np.float64)
@@ -240,6 +243,23 @@ def test_pooled_batches_before_one_update(B):
         compare_update(B, cal, oc, w, "pooled update", check_R=False)
         _, M, n = cal.get_state(want_R=False)
         assert not M.any() and n[0] == 0             # statistics restart empty
+    finally:
+        cal.close()
+
+
+def test_rotation_replaced_while_rows_are_pending(B):
+    """The general path reads the l1 term off M through the current rotation; a rotation swapped in between two batches
+    of one pooled update (set_state with R only) must leave it equal to the sum of the per-batch terms."""
+    w = I.small_workload(320, 200, n_batches=2, seed=123, prox_lambda=0.0)
+    R0 = I.initial_rotation(w)
+    R1 = I.random_orthogonal(w.d, 9).astype(np.float32)[None]
+    oc = O.OracleCalibrator(w.d, 1, w.dtype, R0, 0.0)
+    cal = B.Calibrator(w.d, 1, w.dtype, R0, max_tokens=200)
+    try:
+        compare_step(B, cal, oc, I.batch(w, 0), w, "swap 0")
+        oc.R[:] = R1
+        cal.set_state(R=R1)
+        compare_step(B, cal, oc, I.batch(w, 1), w, "swap 1")      # compares l1 and the objective after both batches
     finally:
         cal.close()
 
