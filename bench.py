@@ -184,6 +184,16 @@ def main():
             "unit": "GB/s", "frac": y_bytes / (acc["quant_error"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
         },
     }
+    if w.dh == 128 and w.dtype == "bf16":
+        # heads of width 128 take the fused step kernel: bound by reading X once (256 bytes per token and head)
+        x_bytes = T * d * 2
+        out["roofline"] = {
+            "bound": "hbm", "kernel": "k_head_step128 + k_head_reduce (the whole step_batch)",
+            "achieved": x_bytes / (gemm_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": x_bytes / (gemm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+            "bytes_per_launch_pair": x_bytes, "ms_per_launch_pair": gemm_ms,
+            "measured_over": "per-kernel HIP events on the library's stream, second pass of the same steps",
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, host[0], R0, args.cpu_sample_tokens or T)
     cal.close()
