@@ -31,7 +31,7 @@ constexpr int kSmemBytes = DH * XROW + TT * XROW + 2 * DH * TROW;
 __device__ __forceinline__ int xoff(int row, int chunk) { return row * XROW + ((chunk ^ (row & 15)) << 4); }
 
 template <bool STORE_SIGNS>
-__global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restrict__ X, int64_t T, int64_t stride, int heads,
+__global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restrict__ X, int64_t T, int64_t stride, int heads,
                                                       const bf16_bits* __restrict__ RopT, float* __restrict__ Mpart,
                                                       int64_t tokens_per_split, float* __restrict__ nrm, int64_t ldn,
                                                       double* __restrict__ L, unsigned long long* __restrict__ rows,
@@ -43,7 +43,7 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
   unsigned char* const sXt = sX + TT * XROW;             // x^ transposed (fp16): row channel, K = token
   unsigned char* const sCt = sXt + DH * TROW;            // corner signs transposed (fp16): row n, K = token
   __shared__ float sW[2][TT];      // 1/(||x|| sqrt(dh)) per token of the tile (0: skipped), by tile parity
-  __shared__ double shd[4];
+  __shared__ double shd[8];
 
   const int h = blockIdx.x, sp = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -56,32 +56,33 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
   {
     const bf16_bits* Rh = RopT + (int64_t)h * DH * DH;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int idx = q * 256 + tid, row = idx >> 4, chunk = idx & 15;
+    for (int q = 0; q < 4; ++q) {
+      const int idx = q * 512 + tid, row = idx >> 4, chunk = idx & 15;
       *reinterpret_cast<uint4*>(sR + xoff(row, chunk)) = *reinterpret_cast<const uint4*>(Rh + row * DH + chunk * 8);
     }
   }
 
-  // Thread -> tile element map of phase 1: row (token) lrow + 16 q, chunk lchunk: the 16 lanes of a row sit in one wavefront.
+  // Thread -> tile element map of phase 1: row (token) lrow + 32 q, chunk lchunk: the 16 lanes of a row sit in one wavefront.
   const int lrow = tid >> 4, lchunk = tid & 15;
   const bf16_bits* Xh = X + (int64_t)h * DH + lchunk * 8;
-  uint4 cur[4], nxt[4];
+  uint4 cur[2], nxt[2];
   auto load_tile = [&](int tile, uint4* dst) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int64_t t = t_begin + (int64_t)tile * TT + lrow + 16 * q;
+    for (int q = 0; q < 2; ++q) {
+      const int64_t t = t_begin + (int64_t)tile * TT + lrow + 32 * q;
       dst[q] = (tile < ntiles && t < t_end) ? *reinterpret_cast<const uint4*>(Xh + t * stride) : make_uint4(0u, 0u, 0u, 0u);
     }
   };
   load_tile(0, cur);
 
-  f32x16 accM[2][2];
+  // 8 wavefronts (2 per SIMD, so that one's LDS and conversion work runs beside the other's MFMAs).
+  const int ti = wave >> 2, nb = wave & 3;        // rotate: tokens [32 ti, +32) x columns [32 nb, +32)
+  const int rm = wave >> 1, cn = 2 * (wave & 1);  // accumulate: channels [32 rm, +32) x columns [32 cn, +64)
+  f32x16 accM[2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) accM[i][j][e] = 0.0f;
+    for (int e = 0; e < 16; ++e) accM[j][e] = 0.0f;
   double l_acc = 0.0;
   unsigned n_rows = 0, n_skipped = 0;
 
@@ -89,8 +90,8 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
     const int par = tile & 1;
     // ---- phase 1: norms, natural copy
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = lrow + 16 * q;
+    for (int q = 0; q < 2; ++q) {
+      const int r = lrow + 32 * q;
       const int64_t t = t_begin + (int64_t)tile * TT + r;
       const uint4 v = cur[q];
       float ss = 0.0f;
@@ -126,14 +127,13 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
     load_tile(tile + 1, nxt);   // in flight during phases 2 and 3
     __syncthreads();
 
-    // ---- phase 2a: scaled transposed copy x^ (fp16).  Thread = (token pair p, chunk pair g): 4-byte LDS writes whose
+    // ---- phase 2a: scaled transposed copy x^ (fp16).  Thread = (token pair p, chunk g): 4-byte LDS writes whose
     // banks differ across the 32 token pairs of a wavefront.
     {
       const int p = tid & 31, g = tid >> 5;
       const float w0 = sW[par][2 * p], w1 = sW[par][2 * p + 1];
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        const int chunk = 2 * g + cc;
+      {
+        const int chunk = g;
         const uint4 a = *reinterpret_cast<const uint4*>(sX + xoff(2 * p, chunk));
         const uint4 b = *reinterpret_cast<const uint4*>(sX + xoff(2 * p + 1, chunk));
         const uint32_t ua[4] = {a.x, a.y, a.z, a.w}, ub[4] = {b.x, b.y, b.z, b.w};
@@ -149,63 +149,51 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
         }
       }
     }
-    // ---- phase 2b: Y = X R_h.  Wavefront w owns output columns n in [32 w, 32 w + 32) for all 64 tokens.
-    f32x16 accY[2];
+    // ---- phase 2b: Y = X R_h.  Wavefront (ti, nb) owns tokens [32 ti, +32) x output columns [32 nb, +32).
+    f32x16 accY;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) accY[i][e] = 0.0f;
+    for (int e = 0; e < 16; ++e) accY[e] = 0.0f;
 #pragma unroll
     for (int kk = 0; kk < DH / 16; ++kk) {
-      const bf16x8 fb = *reinterpret_cast<const bf16x8*>(sR + xoff(32 * wave + col, 2 * kk + half));
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sX + xoff(32 * i + col, 2 * kk + half));
-        accY[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, accY[i], 0, 0, 0);
-      }
+      const bf16x8 fb = *reinterpret_cast<const bf16x8*>(sR + xoff(32 * nb + col, 2 * kk + half));
+      const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sX + xoff(32 * ti + col, 2 * kk + half));
+      accY = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, accY, 0, 0, 0);
     }
-    // accY[i][4 j + ii] = y[token 32 i + 8 j + 4 half + ii][n = 32 wave + col]
+    // accY[4 j + ii] = y[token 32 ti + 8 j + 4 half + ii][n = 32 nb + col]
     {
       // corner signs, transposed: 4 consecutive tokens of column n are 8 bytes
-      const int n = 32 * wave + col;
+      const int n = 32 * nb + col;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < 4; ++j) {
+        uint32_t sg[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          uint32_t s[4];
-#pragma unroll
-          for (int ii = 0; ii < 4; ++ii) s[ii] = accY[i][4 * j + ii] >= 0.0f ? 0x3C00u : 0xBC00u;   // sgn(0) = +1
-          uint2 pk;
-          pk.x = s[0] | (s[1] << 16);
-          pk.y = s[2] | (s[3] << 16);
-          const int tok = 32 * i + 8 * j + 4 * half;
-          *reinterpret_cast<uint2*>(sCt + n * TROW + 2 * tok) = pk;
-          if constexpr (STORE_SIGNS) {
-            const int64_t t = t_begin + (int64_t)tile * TT + tok;
-            if (t < t_end)   // pitch and t are multiples of 4: the 4 tokens are in range together up to the pitch
-              *reinterpret_cast<uint2*>(St + ((int64_t)h * DH + n) * pitch + t) = pk;
-          }
+        for (int ii = 0; ii < 4; ++ii) sg[ii] = accY[4 * j + ii] >= 0.0f ? 0x3C00u : 0xBC00u;   // sgn(0) = +1
+        uint2 pk;
+        pk.x = sg[0] | (sg[1] << 16);
+        pk.y = sg[2] | (sg[3] << 16);
+        const int tok = 32 * ti + 8 * j + 4 * half;
+        *reinterpret_cast<uint2*>(sCt + n * TROW + 2 * tok) = pk;
+        if constexpr (STORE_SIGNS) {
+          const int64_t t = t_begin + (int64_t)tile * TT + tok;
+          if (t < t_end)   // pitch and t are multiples of 4: the 4 tokens are in range together up to the pitch
+            *reinterpret_cast<uint2*>(St + ((int64_t)h * DH + n) * pitch + t) = pk;
         }
+      }
     }
     __syncthreads();
 
-    // ---- phase 3: M_h += x^^T C.  Wavefront w owns the 64 x 64 block (w / 2, w % 2) of M_h.
+    // ---- phase 3: M_h += x^^T C.  Wavefront (rm, cn) owns channels [32 rm, +32) x columns [32 cn, +64) of M_h.
 #pragma unroll
     for (int kk = 0; kk < TT / 16; ++kk) {
-      f16x8 fa[2], fb[2];
+      const f16x8 fa = *reinterpret_cast<const f16x8*>(sXt + (32 * rm + col) * TROW + (2 * kk + half) * 16);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        fa[i] = *reinterpret_cast<const f16x8*>(sXt + (64 * (wave >> 1) + 32 * i + col) * TROW + (2 * kk + half) * 16);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        fb[j] = *reinterpret_cast<const f16x8*>(sCt + (64 * (wave & 1) + 32 * j + col) * TROW + (2 * kk + half) * 16);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) accM[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], accM[i][j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j) {
+        const f16x8 fb = *reinterpret_cast<const f16x8*>(sCt + (32 * (cn + j) + col) * TROW + (2 * kk + half) * 16);
+        accM[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, accM[j], 0, 0, 0);
+      }
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+    for (int q = 0; q < 2; ++q) cur[q] = nxt[q];
     // no barrier here: the next phase 1 writes sX and the other parity of sW, which nobody reads in phase 3;
     // sXt / sCt are written again only after the next tile's first barrier.
   }
@@ -218,18 +206,16 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
     float* Mp = Mpart + ((int64_t)sp * heads + h) * DH * DH;
     float dot = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j) {
+      const int n = 32 * (cn + j) + col;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int n = 64 * (wave & 1) + 32 * j + col;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = 64 * (wave >> 1) + 32 * i + 8 * (e >> 2) + 4 * half + (e & 3);
-          Mp[m * DH + n] = accM[i][j][e];
-          const bf16_bits r = *reinterpret_cast<const bf16_bits*>(sR + xoff(n, m >> 3) + (m & 7) * 2);   // R_op[m][n]
-          dot += accM[i][j][e] * bf16_to_f32(r);
-        }
+      for (int e = 0; e < 16; ++e) {
+        const int m = 32 * rm + 8 * (e >> 2) + 4 * half + (e & 3);
+        Mp[m * DH + n] = accM[j][e];
+        const bf16_bits r = *reinterpret_cast<const bf16_bits*>(sR + xoff(n, m >> 3) + (m & 7) * 2);   // R_op[m][n]
+        dot += accM[j][e] * bf16_to_f32(r);
       }
+    }
     l_acc = (double)dot * 11.313708498984761;   // sqrt(128)
   }
   // ---- statistics of this share: one atomic per workgroup and counter
@@ -239,15 +225,15 @@ __global__ void __launch_bounds__(256) k_head_step128(const bf16_bits* __restric
     __syncthreads();
     if (lane == 0) shd[wave] = l_acc;
     __syncthreads();
-    const double lt = shd[0] + shd[1] + shd[2] + shd[3];
+    const double lt = shd[0] + shd[1] + shd[2] + shd[3] + shd[4] + shd[5] + shd[6] + shd[7];
     __syncthreads();
     if (lane == 0) shd[wave] = r;
     __syncthreads();
-    const double rt = shd[0] + shd[1] + shd[2] + shd[3];
+    const double rt = shd[0] + shd[1] + shd[2] + shd[3] + shd[4] + shd[5] + shd[6] + shd[7];
     __syncthreads();
     if (lane == 0) shd[wave] = k;
     __syncthreads();
-    const double kt = shd[0] + shd[1] + shd[2] + shd[3];
+    const double kt = shd[0] + shd[1] + shd[2] + shd[3] + shd[4] + shd[5] + shd[6] + shd[7];
     if (tid == 0) {
       atomicAdd(L + h, lt);
       atomicAdd(rows + h, (unsigned long long)rt);
@@ -298,10 +284,10 @@ hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, in
     configured = true;
   }
   if (St)
-    hipLaunchKernelGGL(k_head_step128<true>, grid, dim3(256), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
+    hipLaunchKernelGGL(k_head_step128<true>, grid, dim3(512), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
                        L, rows, skipped, nonfinite, St, pitch);
   else
-    hipLaunchKernelGGL(k_head_step128<false>, grid, dim3(256), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
+    hipLaunchKernelGGL(k_head_step128<false>, grid, dim3(512), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
                        L, rows, skipped, nonfinite, St, pitch);
   return hipGetLastError();
 }
