@@ -458,8 +458,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   const bool trace = std::getenv("CONQUR_TRACE") != nullptr;
   if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][0], s));
 
-  HIP_TRY(launch_fill_zero(ctx->fro2, h * sizeof(double), s));
-  HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->fro2, s));
+  HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->dotrm_part, ctx->fro2, s));
 
   const int np_main = 1 + (int)ctx->cfg.polar_precision;
   const SegList& seg_main = np_main == 1 ? kSeg1 : (np_main == 2 ? kSeg3 : kSeg6);

@@ -35,8 +35,8 @@ int dot_rm_partials(int64_t n);
 hipError_t launch_dot_rm(const float* R, const float* M, int heads, int64_t n, int round_bf16, double* part, double* out,
                          hipStream_t s);
 
-// fro2[h] = sum M_h^2 (fro2 must be zero on entry).
-hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s);
+// fro2[h] = sum M_h^2 (overwritten).  part: heads * dot_rm_partials(n) doubles of scratch.
+hipError_t launch_fro2(const float* M, int heads, int64_t n, double* part, double* fro2, hipStream_t s);
 
 // Start of the polar iteration, fused with the operand packing: X0 = (M + lambda*tau*R) / alpha with
 // tau = ||M||_F/sqrt(dh), alpha = ||M||_F (1 + lambda) (a head with M = 0 starts from R itself), written as np bf16

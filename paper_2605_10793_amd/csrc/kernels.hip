@@ -320,7 +320,7 @@ __global__ void __launch_bounds__(256) k_dot_rm(const float* __restrict__ R, con
   if (threadIdx.x == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = acc;
 }
 
-__global__ void __launch_bounds__(256) k_fro2(const float* __restrict__ M, int64_t n, double* __restrict__ fro2) {
+__global__ void __launch_bounds__(256) k_fro2(const float* __restrict__ M, int64_t n, double* __restrict__ part) {
   __shared__ double sh[4];
   const float* m = M + (int64_t)blockIdx.y * n;
   double acc = 0.0;
@@ -329,7 +329,7 @@ __global__ void __launch_bounds__(256) k_fro2(const float* __restrict__ M, int64
     acc += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
   }
   acc = block_sum_d(acc, sh);
-  if (threadIdx.x == 0) atomicAdd(fro2 + blockIdx.y, acc);
+  if (threadIdx.x == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = acc;   // summed in a fixed order afterwards
 }
 
 __global__ void __launch_bounds__(256) k_axpy(float* __restrict__ X, const float* __restrict__ R, int64_t n, float kappa) {
@@ -543,9 +543,12 @@ hipError_t launch_dot_rm(const float* R, const float* M, int heads, int64_t n, i
   return launch_sum_partials(part, blocks, heads, out, s);
 }
 
-hipError_t launch_fro2(const float* M, int heads, int64_t n, double* fro2, hipStream_t s) {
-  hipLaunchKernelGGL(k_fro2, dim3(grid_for(n / 4, 1024), heads), dim3(256), 0, s, M, n, fro2);
-  return hipGetLastError();
+hipError_t launch_fro2(const float* M, int heads, int64_t n, double* part, double* fro2, hipStream_t s) {
+  const int blocks = dot_rm_partials(n);
+  hipLaunchKernelGGL(k_fro2, dim3(blocks, heads), dim3(256), 0, s, M, n, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_sum_partials(part, blocks, heads, fro2, s);
 }
 
 hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s) {
