@@ -14,8 +14,8 @@ enum GemmEpilogue : int {
   EPI_SIGN = 0,  // corner signs, transposed: St[n][m] = +-1 (bf16 or fp16)
   EPI_ACT = 1,   // Y[m][n] = acc, stored as bf16 or fp32 (rotated activations for the quantiser score)
   EPI_F32 = 2,   // C[m][n] = acc (+ C[m][n] if accumulate), fp32
-  EPI_GRAMW = 3, // acc = Gram matrix G (A and B the same operand, so acc is symmetric): W = coef_i*I + coef_g*G
-                 // (+ the planes Padd) written as np_out bf16 split planes and per-wavefront partial sums of (G - I)^2
+  EPI_GRAMW = 3, // acc = Gram matrix G: W = coef_i*I + coef_g*G (+ the planes Padd) written as np_out bf16 split
+                 // planes (natural layout) and per-wavefront partial sums of (G - I)^2
   EPI_XOUT = 4,  // acc = X' (+ Xadd): written as fp32 (C32) and/or np_out bf16 split planes in natural (Pn)
                  // and transposed (Pt) layout -- the operands of the next Gram / apply GEMMs
   EPI_SQUARE = 5, // acc = D^2 (D symmetric, given as two planes Padd): writes acc as one bf16 plane (Pacc) and

@@ -314,8 +314,6 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         }
       }
   } else if constexpr (EPI == EPI_GRAMW) {
-    // acc is symmetric (A and B are the same operand), so the value of element (m, n) is also that of (n, m): a lane's
-    // 4 consecutive rows m0 .. m0+3 of column n are written as 8 contiguous bytes of row n.
     const int64_t boff = (int64_t)bz * g.batchC;
     double rsum = 0.0;
 #pragma unroll
@@ -326,30 +324,19 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         if (n >= g.N) continue;
         float part = 0.0f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int m0 = mw + i * 32 + 8 * q + 4 * half;   // M is a multiple of 4
-          if (m0 >= g.M) continue;
-          float w[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float eye = (m0 + r == n) ? 1.0f : 0.0f;
-            const float d = acc[i][j][4 * q + r] - eye;
-            part += d * d;
-            w[r] = g.coef_i * eye + g.coef_g * acc[i][j][4 * q + r];
-          }
-          const int64_t off = boff + (int64_t)n * g.ldc + m0;
-          for (int p = 0; p < g.np_add; ++p) {
-            const uint2 t = *reinterpret_cast<const uint2*>(g.Padd + p * g.plane_out + off);
-            w[0] += __uint_as_float(t.x << 16); w[1] += __uint_as_float(t.x & 0xffff0000u);
-            w[2] += __uint_as_float(t.y << 16); w[3] += __uint_as_float(t.y & 0xffff0000u);
-          }
+        for (int e = 0; e < 16; ++e) {
+          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (m >= g.M) continue;
+          const float eye = (m == n) ? 1.0f : 0.0f;
+          const float r = acc[i][j][e] - eye;
+          part += r * r;
+          float w = g.coef_i * eye + g.coef_g * acc[i][j][e];
+          const int64_t off = boff + (int64_t)m * g.ldc + n;
+          for (int p = 0; p < g.np_add; ++p) w += bf16_to_f32(g.Padd[p * g.plane_out + off]);
           for (int p = 0; p < g.np_out; ++p) {
-            uint2 t;
-            t.x = f32x2_to_bf16x2(w[0], w[1]);
-            t.y = f32x2_to_bf16x2(w[2], w[3]);
-            w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
-            w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
-            *reinterpret_cast<uint2*>(g.Pn + p * g.plane_out + off) = t;
+            const bf16_bits hb = f32_to_bf16(w);
+            g.Pn[p * g.plane_out + off] = hb;
+            w -= bf16_to_f32(hb);
           }
         }
         rsum += (double)part;
@@ -367,30 +354,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         const int n = nw + j * 32 + col;
         if (n >= g.N) continue;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int m0 = mw + i * 32 + 8 * q + 4 * half;
-          if (m0 >= g.M) continue;
-          const int64_t off = boff + (int64_t)n * g.ldc + m0;   // symmetric, as in EPI_GRAMW
-          const float a0 = acc[i][j][4 * q], a1 = acc[i][j][4 * q + 1], a2 = acc[i][j][4 * q + 2], a3 = acc[i][j][4 * q + 3];
-          uint2 t;
-          t.x = f32x2_to_bf16x2(a0, a1);
-          t.y = f32x2_to_bf16x2(a2, a3);
-          *reinterpret_cast<uint2*>(g.Pacc + off) = t;
-          const uint2 d0 = *reinterpret_cast<const uint2*>(g.Padd + off);
-          const uint2 d1 = *reinterpret_cast<const uint2*>(g.Padd + g.plane_out + off);
-          float w[4];
-          w[0] = g.coef_g * a0 + __uint_as_float(d0.x << 16) + __uint_as_float(d1.x << 16);
-          w[1] = g.coef_g * a1 + __uint_as_float(d0.x & 0xffff0000u) + __uint_as_float(d1.x & 0xffff0000u);
-          w[2] = g.coef_g * a2 + __uint_as_float(d0.y << 16) + __uint_as_float(d1.y << 16);
-          w[3] = g.coef_g * a3 + __uint_as_float(d0.y & 0xffff0000u) + __uint_as_float(d1.y & 0xffff0000u);
-          t.x = f32x2_to_bf16x2(w[0], w[1]);
-          t.y = f32x2_to_bf16x2(w[2], w[3]);
-          *reinterpret_cast<uint2*>(g.Pn + off) = t;
-          w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
-          w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
-          t.x = f32x2_to_bf16x2(w[0], w[1]);
-          t.y = f32x2_to_bf16x2(w[2], w[3]);
-          *reinterpret_cast<uint2*>(g.Pn + g.plane_out + off) = t;
+        for (int e = 0; e < 16; ++e) {
+          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (m >= g.M) continue;
+          const int64_t off = boff + (int64_t)m * g.ldc + n;
+          const float a = acc[i][j][e];
+          g.Pacc[off] = f32_to_bf16(a);
+          float w = g.coef_g * a + bf16_to_f32(g.Padd[off]) + bf16_to_f32(g.Padd[g.plane_out + off]);
+          const bf16_bits h0 = f32_to_bf16(w);
+          g.Pn[off] = h0;
+          g.Pn[g.plane_out + off] = f32_to_bf16(w - bf16_to_f32(h0));
         }
       }
   } else if constexpr (EPI == EPI_FRO2) {
@@ -522,9 +495,6 @@ int gemm_num_workgroups(int M, int N, int batch) {
 hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStream_t stream) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
       batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
-    return hipErrorInvalidValue;
-  // the symmetric epilogues store element (m, n) at (n, m): both operands must be the same matrix
-  if ((epi == EPI_GRAMW || epi == EPI_SQUARE) && (a.A != a.B || a.M != a.N || a.lda != a.ldb || (a.M & 3) || (a.ldc & 3)))
     return hipErrorInvalidValue;
   switch (epi) {
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
