@@ -263,24 +263,37 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   const int mw = m0 + wm * WM, nw = n0 + wn * WN;
 
   if constexpr (EPI == EPI_SIGN) {
+    // St is the transpose of the accumulator tile.  Storing it straight from the registers gives every lane 8 bytes of
+    // a different row (64 cache lines per store instruction); instead each wavefront transposes its WM x WN block
+    // through its own slice of the (now idle) stage memory and stores whole 16-byte chunks, 8 or 16 lanes per row.
     bf16_bits* St = reinterpret_cast<bf16_bits*>(g.C) + (int64_t)bz * g.batchC;
     const uint32_t one = g.sign_f16 ? 0x3C00u : 0x3F80u;
+    constexpr int SROW = WM * 2;                      // bytes per staged row (one output column n, WM tokens)
+    constexpr int CPR = WM / 8;                       // 16-byte chunks per staged row, XOR swizzled by the row
+    static_assert(NW * WN * SROW <= NSTAGE * STAGE && (CPR & (CPR - 1)) == 0, "sign staging fits the stage memory");
+    unsigned char* stg = smem + wave * (WN * SROW);
+    __syncthreads();                                  // every wavefront has finished reading operand tiles
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int mb = mw + i * 32 + 8 * q + 4 * half;
           const f32x16& a = acc[i][j];
           uint2 v;  // +1 with the sign bit of each accumulator (sgn(+-0) = +1, so test >= 0)
           v.x = (a[4 * q + 0] >= 0.0f ? one : one | 0x8000u) | ((a[4 * q + 1] >= 0.0f ? one : one | 0x8000u) << 16);
           v.y = (a[4 * q + 2] >= 0.0f ? one : one | 0x8000u) | ((a[4 * q + 3] >= 0.0f ? one : one | 0x8000u) << 16);
-          if (mb < g.st_rows_valid) *reinterpret_cast<uint2*>(St + (int64_t)n * g.ldc + mb) = v;
+          const int r = j * 32 + col, c = i * 4 + q;   // tokens 8 c + 4 half .. + 3 of row r
+          *reinterpret_cast<uint2*>(stg + r * SROW + ((c ^ (r & (CPR - 1))) << 4) + 8 * half) = v;
         }
-      }
+    // the slice is private to the wavefront: its own LDS writes are visible to it after the wait the compiler inserts
+#pragma unroll
+    for (int it2 = 0; it2 < WN * CPR / 64; ++it2) {
+      const int idx = it2 * 64 + lane, r = idx / CPR, c = idx % CPR;
+      const int n = nw + r, m = mw + c * 8;
+      const uint4 v = *reinterpret_cast<const uint4*>(stg + r * SROW + ((c ^ (r & (CPR - 1))) << 4));
+      if (n < g.N && m < g.st_rows_valid) *reinterpret_cast<uint4*>(St + (int64_t)n * g.ldc + m) = v;
+    }
   } else if constexpr (EPI == EPI_ACT) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
