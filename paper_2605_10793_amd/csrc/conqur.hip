@@ -341,9 +341,9 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
   ctx->last_signs_valid = true;
   {
     StageTimer tm(ctx, ST_PREP);
-    HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, ctx->cnt, s));
+    HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, s));
     HIP_TRY(launch_transpose_scale(X, ctx->f32, T, Tk, stride, ctx->d, ctx->dh, ctx->w, ctx->tmax, ctx->Xt, ctx->pitch,
-                                   (int64_t)ctx->d * ctx->pitch, ctx->np, s));
+                                   (int64_t)ctx->d * ctx->pitch, ctx->np, ctx->cnt, s));
     if (ctx->f32)
       HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
   }

@@ -9,16 +9,17 @@ namespace conqur {
 
 // n_i = ||x_i||_2 over each head slice; w_i = 1/(n_i*sqrt(dh)), or 0 for a row that is
 // all zero or holds a non-finite value (then nrm = 0 and *nonfinite is raised for NaN/Inf).
-// cnt: [heads][kCountSlots][2] counters (rows that enter M, rows skipped), row i counts into slot i % kCountSlots.
-constexpr int kCountSlots = 64;
 hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh,
-                            float* nrm, float* w, int64_t ldn, int* nonfinite, unsigned long long* cnt, hipStream_t s);
+                            float* nrm, float* w, int64_t ldn, int* nonfinite, hipStream_t s);
 
 // Xt[p][k][i] = x_ik * w_{head(k), i} for i < T, 0 for T <= i < Tk.  np = 1 (bf16 activations):
 // one fp16 plane; np = 3 (fp32 activations): three bf16 split planes (exact).
+// Also counts the rows (w != 0: entered M, w == 0: skipped) into cnt [heads][kCountSlots][2], the token block b
+// into slot b % kCountSlots.
+constexpr int kCountSlots = 64;
 hipError_t launch_transpose_scale(const void* X, int x_is_f32, int64_t T, int64_t Tk, int64_t stride, int d, int dh,
                                   const float* w, int64_t ldn, bf16_bits* Xt, int64_t pitch, int64_t plane, int np,
-                                  hipStream_t s);
+                                  unsigned long long* cnt, hipStream_t s);
 
 // Xs[p][i][k] = split_p(x_ik), fp32 activations only (3 planes).
 hipError_t launch_split_rows(const float* X, int64_t T, int64_t stride, int d, bf16_bits* Xs, int64_t plane,

@@ -40,7 +40,7 @@ __device__ __forceinline__ double block_sum_d(double v, double* sh) {
 template <bool F32>
 __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, int64_t T, int64_t stride, int heads, int dh,
                                                    float* __restrict__ nrm, float* __restrict__ w, int64_t ldn,
-                                                   int* __restrict__ nonfinite, unsigned long long* __restrict__ cnt) {
+                                                   int* __restrict__ nonfinite) {
   const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (gw >= T * heads) return;
@@ -91,9 +91,6 @@ __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, i
     }
     nrm[(int64_t)h * ldn + i] = n;
     w[(int64_t)h * ldn + i] = wi;
-    // rows that enter M / rows skipped, counted into one of kCountSlots slots per head so that the atomics of a
-    // batch spread over many addresses (atomics from all XCDs on one address serialise)
-    atomicAdd(cnt + ((int64_t)h * kCountSlots + (i % kCountSlots)) * 2 + (n > 0.0f ? 0 : 1), 1ull);
   }
 }
 
@@ -101,7 +98,8 @@ __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, i
 template <bool F32, int NP>
 __global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict__ X, int64_t T, int64_t stride, int d, int dh,
                                                          const float* __restrict__ w, int64_t ldn,
-                                                         bf16_bits* __restrict__ Xt, int64_t pitch, int64_t plane) {
+                                                         bf16_bits* __restrict__ Xt, int64_t pitch, int64_t plane,
+                                                         unsigned long long* __restrict__ cnt) {
   // bf16 input: the tile holds the finished fp16 values (8.3 KiB, so that this kernel's workgroups still fit
   // beside a GEMM workgroup that owns 144 KiB of the CU's LDS); fp32 input: fp32 values, split after the transpose
   using TileT = typename std::conditional<NP == 1, bf16_bits, float>::type;
@@ -109,6 +107,21 @@ __global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict_
   const int64_t i0 = (int64_t)blockIdx.x * 64;
   const int k0 = blockIdx.y * 64;
   const int t = threadIdx.x;
+  if (t < 64) {
+    // The workgroup that holds a head's first column also counts that head's rows (entered M / skipped) among its 64
+    // tokens: two ballots by one wavefront, added to one of kCountSlots slots per head so that a batch's atomics
+    // spread over many addresses (atomics from all XCDs on one address serialise).
+    for (int h = (k0 + dh - 1) / dh; h * dh < k0 + 64 && h * dh < d; ++h) {
+      const int64_t i = i0 + t;
+      const float wv = i < T ? w[(int64_t)h * ldn + i] : 0.0f;
+      const unsigned long long in = __ballot(i < T && wv != 0.0f), out = __ballot(i < T && wv == 0.0f);
+      if (t == 0) {
+        unsigned long long* slot = cnt + ((int64_t)h * kCountSlots + (blockIdx.x % kCountSlots)) * 2;
+        if (in) atomicAdd(slot, (unsigned long long)__popcll(in));
+        if (out) atomicAdd(slot + 1, (unsigned long long)__popcll(out));
+      }
+    }
+  }
   {
     const int c = t & 7;
 #pragma unroll
@@ -462,24 +475,24 @@ inline int grid_for(int64_t items, int cap = 4096) {
 }  // namespace
 
 hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh, float* nrm, float* w,
-                            int64_t ldn, int* nonfinite, unsigned long long* cnt, hipStream_t s) {
+                            int64_t ldn, int* nonfinite, hipStream_t s) {
   const int64_t waves = T * heads;
   dim3 grid((unsigned)((waves + 3) / 4));
   if (x_is_f32)
-    hipLaunchKernelGGL(k_row_norms<true>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite, cnt);
+    hipLaunchKernelGGL(k_row_norms<true>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite);
   else
-    hipLaunchKernelGGL(k_row_norms<false>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite, cnt);
+    hipLaunchKernelGGL(k_row_norms<false>, grid, dim3(256), 0, s, X, T, stride, heads, dh, nrm, w, ldn, nonfinite);
   return hipGetLastError();
 }
 
 hipError_t launch_transpose_scale(const void* X, int x_is_f32, int64_t T, int64_t Tk, int64_t stride, int d, int dh,
                                   const float* w, int64_t ldn, bf16_bits* Xt, int64_t pitch, int64_t plane, int np,
-                                  hipStream_t s) {
+                                  unsigned long long* cnt, hipStream_t s) {
   dim3 grid((unsigned)(Tk / 64), (unsigned)((d + 63) / 64));
   if (x_is_f32 && np == 3)
-    hipLaunchKernelGGL((k_transpose_scale<true, 3>), grid, dim3(256), 0, s, X, T, stride, d, dh, w, ldn, Xt, pitch, plane);
+    hipLaunchKernelGGL((k_transpose_scale<true, 3>), grid, dim3(256), 0, s, X, T, stride, d, dh, w, ldn, Xt, pitch, plane, cnt);
   else if (!x_is_f32 && np == 1)
-    hipLaunchKernelGGL((k_transpose_scale<false, 1>), grid, dim3(256), 0, s, X, T, stride, d, dh, w, ldn, Xt, pitch, plane);
+    hipLaunchKernelGGL((k_transpose_scale<false, 1>), grid, dim3(256), 0, s, X, T, stride, d, dh, w, ldn, Xt, pitch, plane, cnt);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
