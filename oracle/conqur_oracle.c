@@ -379,3 +379,81 @@ int oq_quant_error(const float* X, uint64_t T, uint64_t d, uint64_t heads, uint6
   free(rs); free(re);
   return 0;
 }
+
+/*
+ * Per-token asymmetric (zero-point) b-bit fake-quantisation error of the rotated rows
+ * (App. B, "per-tensor asymmetric (zeropoint) quantizer": the affine range
+ * [min_j y_j, max_j y_j] is mapped onto the unsigned grid {0, ..., 2^b - 1}; App. C
+ * evaluates activations with a clipping ratio of 0.9).
+ *   y as in oq_quant_error (x R_op per head, stored in the activation dtype).
+ *   Per token, over the whole row of width d:
+ *     lo = clip * min_j y_j,  hi = clip * max_j y_j        (clip in (0, 1]; 1 = the appendix's quantiser)
+ *     D = (hi - lo) / (2^b - 1),  zeta = -rint(lo / D)     (integer zero point: lo lands on code 0)
+ *     code_j = clamp(rint(y_j / D) + zeta, 0, 2^b - 1),  q_j = D * (code_j - zeta)
+ *   A row with hi = lo (constant row) has the single level lo: q_j = lo.
+ * As for the symmetric quantiser the integer code is decided in fp32 (lo, hi, D, y / D
+ * are single-precision operations); the squared error is summed in fp64.
+ *   out: *sse = sum (y - q)^2, *energy = sum y^2, row_sse[T] optional, codes[T][d] optional (uint8).
+ */
+int oq_quant_error_zp(const float* X, uint64_t T, uint64_t d, uint64_t heads, uint64_t row_stride,
+                      const float* R_op, int dtype, int bits, float clip, double* sse, double* energy,
+                      double* row_sse, uint8_t* codes) {
+  if (!X || !R_op || heads == 0 || d % heads || row_stride < d || bits < 2 || bits > 8 || !(clip > 0.0f) || clip > 1.0f)
+    return -1;
+  const uint64_t dh = d / heads;
+  const float qtop = (float)((1 << bits) - 1);
+  double* rs = (double*)calloc(T, sizeof(double));
+  double* re = (double*)calloc(T, sizeof(double));
+  if (!rs || !re) { free(rs); free(re); return -1; }
+#pragma omp parallel
+  {
+    double* y = (double*)malloc(sizeof(double) * d);
+#pragma omp for schedule(static)
+    for (uint64_t i = 0; i < T; ++i) {
+      for (uint64_t h = 0; h < heads; ++h) {
+        const float* x = X + i * row_stride + h * dh;
+        const float* Rh = R_op + h * dh * dh;
+        double* yh = y + h * dh;
+        for (uint64_t j = 0; j < dh; ++j) yh[j] = 0.0;
+        for (uint64_t k = 0; k < dh; ++k) {
+          const double xik = (double)x[k];
+          for (uint64_t j = 0; j < dh; ++j) yh[j] += xik * (double)Rh[k * dh + j];
+        }
+      }
+      float mn = 0.0f, mx = 0.0f;
+      for (uint64_t j = 0; j < d; ++j) {
+        y[j] = dtype == 1 ? oq_round_bf16_f64(y[j]) : (double)(float)y[j];
+        const float v = (float)y[j];
+        if (j == 0 || v < mn) mn = v;
+        if (j == 0 || v > mx) mx = v;
+      }
+      const float lo = clip * mn, hi = clip * mx;
+      const float delta = (hi - lo) / qtop;
+      const float zeta = delta > 0.0f ? -rintf(lo / delta) : 0.0f;
+      double s = 0.0, e = 0.0;
+      for (uint64_t j = 0; j < d; ++j) {
+        double q;
+        float code = 0.0f;
+        if (delta > 0.0f) {
+          code = rintf((float)y[j] / delta) + zeta;
+          if (code > qtop) code = qtop;
+          if (code < 0.0f) code = 0.0f;
+          q = (double)delta * ((double)code - (double)zeta);
+        } else {
+          q = (double)lo;
+        }
+        s += (y[j] - q) * (y[j] - q);
+        e += y[j] * y[j];
+        if (codes) codes[i * d + j] = (uint8_t)code;
+      }
+      rs[i] = s; re[i] = e;
+    }
+    free(y);
+  }
+  double S = 0.0, E = 0.0;
+  for (uint64_t i = 0; i < T; ++i) { S += rs[i]; E += re[i]; if (row_sse) row_sse[i] = rs[i]; }
+  if (sse) *sse = S;
+  if (energy) *energy = E;
+  free(rs); free(re);
+  return 0;
+}

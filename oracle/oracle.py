@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.oq_procrustes.argtypes = [p, p, u64, dbl, p, p]
         L.oq_quant_error.restype = i32
         L.oq_quant_error.argtypes = [p, u64, u64, u64, u64, p, i32, i32, p, p, p, p]
+        L.oq_quant_error_zp.restype = i32
+        L.oq_quant_error_zp.argtypes = [p, u64, u64, u64, u64, p, i32, i32, ctypes.c_float, p, p, p, p]
         _lib = L
     return _lib
 
@@ -157,4 +159,20 @@ class OracleCalibrator:
                                   ctypes.byref(sse), ctypes.byref(en), _ptr(rows), _ptr(codes))
         if rc != 0:
             raise RuntimeError("oq_quant_error failed")
+        return sse.value, en.value, rows, codes
+
+    def quant_error_zp(self, X: np.ndarray, bits: int = 4, clip: float = 1.0, want_rows: bool = False,
+                       want_codes: bool = False):
+        """Asymmetric (zero-point) per-token quantiser of App. B with the clipping ratio of App. C."""
+        X = np.ascontiguousarray(X, dtype=np.float32)
+        T, stride = X.shape
+        sse = ctypes.c_double(0.0); en = ctypes.c_double(0.0)
+        rows = np.empty(T, dtype=np.float64) if want_rows else None
+        codes = np.empty((T, self.d), dtype=np.uint8) if want_codes else None
+        Rop = self.R_op
+        rc = lib().oq_quant_error_zp(_ptr(X), T, self.d, self.heads, stride, _ptr(Rop),
+                                     1 if self.dtype == "bf16" else 0, bits, ctypes.c_float(clip),
+                                     ctypes.byref(sse), ctypes.byref(en), _ptr(rows), _ptr(codes))
+        if rc != 0:
+            raise RuntimeError("oq_quant_error_zp failed")
         return sse.value, en.value, rows, codes

@@ -414,3 +414,79 @@ def test_c1_stream_runs_and_improves():
         assert st["orth_err"] < 1e-10 and np.isclose(st["inner"], st["nuclear"], rtol=1e-10)
     after = oc.quant_error(X0)
     assert objs[-1] < objs[0] and after[0] / after[1] < 0.6 * before[0] / before[1]
+
+
+# --------------------------------------------------------------------------- zero-point quantiser (App. B)
+
+def test_zeropoint_hand_computed_rows(golden):
+    assert int(golden["zp_levels_b4"]) == 15
+    oc = O.OracleCalibrator(3, 1, "f32", np.eye(3, dtype=np.float32))
+    # b = 2: grid {0..3}; range [-1.5, 1.5] -> D = 1, zeta = -rint(-1.5) = 2 (tie to even);
+    # -1.5 -> rint -2 -> code 0 -> -2 (err .5); 0 -> code 2 -> 0; 1.5 -> rint 2 -> code 4 -> clamp 3 -> 1 (err .5)
+    sse, en, rows, codes = oc.quant_error_zp(np.array([[-1.5, 0.0, 1.5]], dtype=np.float32), 2, 1.0, True, True)
+    assert codes[0].tolist() == [0, 2, 3] and np.isclose(sse, 0.5, rtol=1e-12) and np.isclose(en, 4.5)
+    # clip 0.75 on [-2..2], b = 2: lo = -1.5, hi = 1.5, D = 1, zeta = 2: codes 0,1,2,3,3 -> -2,-1,0,1,1 -> SSE = 1
+    oc5 = O.OracleCalibrator(5, 1, "f32", np.eye(5, dtype=np.float32))
+    sse, _, _, codes = oc5.quant_error_zp(np.array([[-2.0, -1.0, 0.0, 1.0, 2.0]], dtype=np.float32), 2, 0.75, False, True)
+    assert codes[0].tolist() == [0, 1, 2, 3, 3] and np.isclose(sse, 1.0, rtol=1e-12)
+    # b = 4 on 0..15: D = 1, zeta = 0, every entry is a level
+    oc16 = O.OracleCalibrator(16, 1, "f32", np.eye(16, dtype=np.float32))
+    sse, _, _, codes = oc16.quant_error_zp(np.arange(16, dtype=np.float32)[None, :], 4, 1.0, False, True)
+    assert sse == 0.0 and codes[0].tolist() == list(range(16))
+    # constant and zero rows: a single level, no error at clip 1
+    sse, en, _, _ = oc16.quant_error_zp(np.stack([np.full(16, 2.5, np.float32), np.zeros(16, np.float32)]), 4, 1.0)
+    assert sse == 0.0 and np.isclose(en, 16 * 6.25)
+
+
+def test_zeropoint_grid_rows_shift_and_scale():
+    """Rows on the grid have zero error; a shift by whole steps moves only the zero point; scaling by 2^k scales the SSE by 4^k."""
+    d = 64
+    g = np.random.Generator(np.random.Philox(key=15))
+    codes = g.integers(0, 16, size=(8, d)).astype(np.float64)
+    codes[:, 0] = 0; codes[:, 1] = 15                          # both ends of the grid are hit
+    oc = O.OracleCalibrator(d, 1, "f32", np.eye(d, dtype=np.float32))
+    for zeta in (0, 3, 9, 15, -4, 40):
+        Y = ((codes - zeta) * 0.25).astype(np.float32)
+        sse, _, _, got = oc.quant_error_zp(Y, 4, 1.0, False, True)
+        assert sse == 0.0 and np.array_equal(got, codes.astype(np.uint8)), zeta
+    halves = (g.integers(0, 31, size=(8, d)) * 0.5)
+    halves[:, 0] = 0.0; halves[:, 1] = 15.0                    # D = 1; half-integers round to even
+    base, _, rows0, _ = oc.quant_error_zp(halves.astype(np.float32), 4, 1.0, True)
+    odd_halves = (np.round(halves * 2) % 2 == 1).sum()
+    assert np.isclose(base, 0.25 * odd_halves, rtol=1e-12)
+    shifted, _, rows1, _ = oc.quant_error_zp((halves + 8.0).astype(np.float32), 4, 1.0, True)   # 8 = an even number of steps
+    assert np.array_equal(rows0, rows1)
+    scaled, _, _, _ = oc.quant_error_zp((halves * 8.0).astype(np.float32), 4, 1.0)
+    assert scaled == 64.0 * base
+
+
+def test_zeropoint_bounds_from_appendix_b(golden):
+    """||Q_zp(y)-y||^2 <= d D^2/4 with D = (max-min)/(2^b-1), and max-min <= 2 ||y||_inf (App. B); clipping only
+    adds the overshoot of the entries outside [clip*min, clip*max]."""
+    d = 256
+    w = I.small_workload(d, 300, seed=21)
+    X = I.batch(w, 0)
+    R = I.initial_rotation(w)
+    oc = O.OracleCalibrator(d, 1, "bf16", R)
+    sse, en, rows, codes = oc.quant_error_zp(X, 4, 1.0, True, True)
+    Y = I.round_to_bf16((X.astype(np.float64) @ oc.R_op[0].astype(np.float64)).astype(np.float32)).astype(np.float64)
+    rng = Y.max(axis=1) - Y.min(axis=1)
+    delta = rng / golden["zp_levels_b4"]
+    assert np.all(rows <= d * delta ** 2 / 4 * (1 + 1e-6))
+    assert np.all(rng <= 2 * np.abs(Y).max(axis=1))
+    assert codes.min() == 0 and codes.max() == 15
+    assert np.isclose(en, (Y ** 2).sum(), rtol=1e-12)
+    assert 0.5 < rows.sum() / (d * delta ** 2 / 12).sum() < 1.2          # uniform rounding noise on dense rows
+    # the symmetric quantiser spends its 15 levels on [-max|y|, max|y|]: never a finer step than the zero-point one
+    s_sym, _, rows_sym, _ = oc.quant_error(X, 4, True, False)
+    assert np.all(2 * np.abs(Y).max(axis=1) / 14 >= delta * (1 - 1e-12))
+    # clipping at the evaluation ratio: entries inside the clipped range keep |err| <= D_c/2, the others overshoot
+    c = golden["act_clip_ratio"]
+    _, _, rows_c, codes_c = oc.quant_error_zp(X, 4, c, True, True)
+    lo, hi = c * Y.min(axis=1, keepdims=True), c * Y.max(axis=1, keepdims=True)
+    dc = (hi - lo) / 15
+    inside = (Y >= lo) & (Y <= hi)
+    over = np.where(Y > hi, Y - hi, np.where(Y < lo, lo - Y, 0.0))
+    upper = (inside * (dc / 2) ** 2 + (~inside) * (over + dc / 2) ** 2).sum(axis=1)
+    assert np.all(rows_c <= upper * (1 + 1e-5) + 1e-12)
+    assert np.all(rows_c >= (over ** 2 * 0.99).sum(axis=1) - 1e-9 - (2 * over * dc / 2).sum(axis=1))
