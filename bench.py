@@ -138,6 +138,14 @@ def main():
     probe = cal.clock_probe()       # of the last step's two GEMM launches
     for k in acc:
         acc[k] /= K
+    # the zero-point (asymmetric) quantiser score at the paper's evaluation clipping ratio: same rotate GEMM, the
+    # error kernel tracks min and max instead of max |y|
+    zp_ms, zp_rel = 0.0, 0.0
+    for i in range(K):
+        s_zp, e_zp = cal.quant_error_zp(dev[i % n_distinct], 4, 0.9)
+        zp_ms += cal.timing()["quant_error"]
+        zp_rel = s_zp / e_zp
+    zp_ms /= K
     step_ms = whole["step"]
     gemm_ms = acc["rotate"] + acc["accumulate"]
     dh = w.dh
@@ -183,6 +191,10 @@ def main():
             "bound": "hbm", "achieved": y_bytes / (acc["quant_error"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
             "unit": "GB/s", "frac": y_bytes / (acc["quant_error"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
         },
+    }
+    out["roofline_quant_error_zp"] = {
+        "bound": "hbm", "achieved": y_bytes / (zp_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": y_bytes / (zp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "ms": zp_ms, "clip_ratio": 0.9, "int4_rel_err": zp_rel,
     }
     if w.dh == 128 and w.dtype == "bf16":
         # heads of width 128 take the fused step kernel: bound by reading X once (256 bytes per token and head)

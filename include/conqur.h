@@ -140,6 +140,18 @@ conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X_dev, uint64_t T,
                                  uint32_t bits, double* sse_host, double* energy_host);
 
 /*
+ * The same score with the per-token asymmetric (zero-point) quantiser (App. B, "zeropoint
+ * quantizer"; App. C evaluates activations with clipping ratio 0.9): per token, over the
+ * whole row, lo = clip_ratio * min_j y_j, hi = clip_ratio * max_j y_j, D = (hi - lo) /
+ * (2^bits - 1), integer zero point zeta = -round_half_even(lo / D), code = round_half_even(y / D)
+ * + zeta clamped to [0, 2^bits - 1], q = D * (code - zeta); a constant row has the single
+ * level lo.  clip_ratio in (0, 1] (1: the appendix's quantiser).  Arguments, outputs,
+ * synchronisation and errors as conqur_quant_error.
+ */
+conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems,
+                                    uint32_t bits, float clip_ratio, double* sse_host, double* energy_host);
+
+/*
  * Copy state to the host / replace it (checkpointing, and teacher-forced parity
  * tests).  R_host, M_host: HOST, heads*dh*dh floats or NULL.  n_rows_host: HOST,
  * `heads` entries or NULL.  set_state(R) also refreshes the rotate operand;

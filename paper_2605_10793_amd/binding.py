@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
-    "conqur_quant_error", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
+    "conqur_quant_error", "conqur_quant_error_zp", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
     "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
@@ -71,6 +71,9 @@ def load() -> ctypes.CDLL:
         L.conqur_update_rotation.argtypes = [vp, vp]
         L.conqur_quant_error.restype = i32
         L.conqur_quant_error.argtypes = [vp, vp, u64, u64, u32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.conqur_quant_error_zp.restype = i32
+        L.conqur_quant_error_zp.argtypes = [vp, vp, u64, u64, u32, ctypes.c_float, ctypes.POINTER(ctypes.c_double),
+                                            ctypes.POINTER(ctypes.c_double)]
         L.conqur_get_state.restype = i32
         L.conqur_get_state.argtypes = [vp, vp, vp, vp]
         L.conqur_set_state.restype = i32
@@ -168,6 +171,13 @@ class Calibrator:
         p, T, stride = self._x(X)
         sse, en = ctypes.c_double(), ctypes.c_double()
         self._check(self._lib.conqur_quant_error(self._h, p, T, stride, bits, ctypes.byref(sse), ctypes.byref(en)))
+        return sse.value, en.value
+
+    def quant_error_zp(self, X, bits: int = 4, clip_ratio: float = 1.0) -> Tuple[float, float]:
+        p, T, stride = self._x(X)
+        sse, en = ctypes.c_double(), ctypes.c_double()
+        self._check(self._lib.conqur_quant_error_zp(self._h, p, T, stride, bits, ctypes.c_float(clip_ratio),
+                                                    ctypes.byref(sse), ctypes.byref(en)))
         return sse.value, en.value
 
     def get_state(self, want_R: bool = True, want_M: bool = True):

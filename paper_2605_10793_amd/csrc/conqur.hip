@@ -725,11 +725,12 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   return CONQUR_OK;
 }
 
-conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, uint32_t bits,
-                                 double* sse, double* energy) {
+static conqur_status quant_error_impl(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, uint32_t bits,
+                                      int zero_point, float clip, double* sse, double* energy) {
   conqur_status st = check_x(ctx, X, T64, stride64);
   if (st != CONQUR_OK) return st;
   if (bits < 2 || bits > 8) return fail(ctx, CONQUR_EINVAL, "bits must be in [2, 8]");
+  if (zero_point && (!(clip > 0.0f) || clip > 1.0f)) return fail(ctx, CONQUR_EINVAL, "clip_ratio must be in (0, 1]");
   if (!sse || !energy) return fail(ctx, CONQUR_EINVAL, "sse_host / energy_host is NULL");
   HIP_TRY(hipSetDevice(ctx->cfg.device));
   const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
@@ -747,7 +748,8 @@ conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T64, u
   }
   {
     StageTimer tm(ctx, ST_QERR);
-    HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, ctx->row_sse, ctx->row_en, ctx->qsum, s));
+    HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, zero_point, clip, ctx->row_sse, ctx->row_en,
+                               ctx->qsum, s));
   }
   }
   double host[2] = {0.0, 0.0};
@@ -756,6 +758,16 @@ conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T64, u
   *sse = host[0];
   *energy = host[1];
   return CONQUR_OK;
+}
+
+conqur_status conqur_quant_error(conqur_ctx* ctx, const void* X, uint64_t T, uint64_t stride, uint32_t bits, double* sse,
+                                 double* energy) {
+  return quant_error_impl(ctx, X, T, stride, bits, 0, 1.0f, sse, energy);
+}
+
+conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X, uint64_t T, uint64_t stride, uint32_t bits,
+                                    float clip_ratio, double* sse, double* energy) {
+  return quant_error_impl(ctx, X, T, stride, bits, 1, clip_ratio, sse, energy);
 }
 
 conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, uint64_t* n_rows) {

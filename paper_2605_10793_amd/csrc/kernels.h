@@ -79,10 +79,10 @@ struct PolarSchedule {
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
                                 bf16_bits* Pn, bf16_bits* Pt, int64_t plane, hipStream_t s);
 
-// Per-row symmetric fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse /
-// row_en, then their sums over rows: out[0] = SSE, out[1] = energy.
-hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,
-                              float* row_en, double* out, hipStream_t s);
+// Per-row fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse / row_en, then their sums over rows:
+// out[0] = SSE, out[1] = energy.  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
+hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
+                              float* row_sse, float* row_en, double* out, hipStream_t s);
 
 // out[h] = sum of part[h][0..n) for h < heads, fixed order.
 hipError_t launch_sum_partials(const double* part, int n, int heads, double* out, hipStream_t s);

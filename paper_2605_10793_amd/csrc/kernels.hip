@@ -359,12 +359,14 @@ __global__ void __launch_bounds__(256) k_axpy(float* __restrict__ X, const float
 // in registers (4 chunks per thread = 8192 bf16 / 4096 fp32 elements; longer rows re-read
 // the tail, which then comes from cache).  Two barriers per row (maximum, sums); per-row
 // results go to row_sse / row_en.
-template <bool F32>
+// ZP: the zero-point quantiser of App. B instead of the symmetric one: range [clip*min, clip*max] on the unsigned grid
+// {0 .. qmax}, D = range / qmax, integer zero point zeta = -rint(lo / D), code = clamp(rint(y / D) + zeta, 0, qmax).
+template <bool F32, bool ZP>
 __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y, int64_t T, int64_t ld, int d, float qmax,
-                                                     float* __restrict__ row_sse, float* __restrict__ row_en) {
+                                                     float clip, float* __restrict__ row_sse, float* __restrict__ row_en) {
   constexpr int EPC = F32 ? 4 : 8;  // elements per 16-byte chunk
   constexpr int NC = 4;             // chunks cached per thread
-  __shared__ float shm[4], shs[4], she[4];
+  __shared__ float shm[4], shn[4], shs[4], she[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = blockIdx.x;
   const int nch = d / EPC;
@@ -377,43 +379,73 @@ __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y,
   };
   const uint4* y = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(Y) + row * ld * (F32 ? 4 : 2));
   uint4 cache[NC];
-  float amax = 0.0f;
+  // symmetric: amax = max |y|.  ZP: amax = max y, amin = -min y (both start from the row's first element)
+  float amax = 0.0f, amin = 0.0f;
+  if constexpr (ZP) {
+    float f[EPC];
+    expand(y[0], f);
+    amax = f[0];
+    amin = -f[0];
+  }
+  auto track = [&](const uint4& v) {
+    float f[EPC];
+    expand(v, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      if constexpr (ZP) {
+        amax = fmaxf(amax, f[e]);
+        amin = fmaxf(amin, -f[e]);
+      } else {
+        amax = fmaxf(amax, fabsf(f[e]));
+      }
+    }
+  };
 #pragma unroll
   for (int q = 0; q < NC; ++q) {
     const int c = threadIdx.x + 256 * q;
     cache[q] = make_uint4(0, 0, 0, 0);
     if (c < nch) {
       cache[q] = y[c];
-      float f[EPC];
-      expand(cache[q], f);
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));
+      track(cache[q]);
     }
   }
-  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) {
-    float f[EPC];
-    expand(y[c], f);
-#pragma unroll
-    for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));
-  }
+  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) track(y[c]);
   amax = wave_max(amax);
-  if (lane == 0) shm[wave] = amax;
+  if constexpr (ZP) amin = wave_max(amin);
+  if (lane == 0) { shm[wave] = amax; shn[wave] = amin; }
   __syncthreads();
   amax = fmaxf(fmaxf(shm[0], shm[1]), fmaxf(shm[2], shm[3]));
+  if constexpr (ZP) amin = fmaxf(fmaxf(shn[0], shn[1]), fmaxf(shn[2], shn[3]));
   // D = max / qmax; the code is decided in fp32 as round-half-even(y * (1/D)) with the
   // correctly rounded reciprocal (a division per element would make this kernel
   // ALU bound instead of HBM bound); it can differ from round(y / D) only within an
   // ulp of a rounding tie, where both codes give the same squared error.
-  const float delta = amax / qmax;
-  const float inv_delta = amax > 0.0f ? 1.0f / delta : 0.0f;
+  float delta, inv_delta, zeta = 0.0f, lo = 0.0f;
+  if constexpr (ZP) {
+    lo = clip * -amin;
+    const float hi = clip * amax;
+    delta = (hi - lo) / qmax;
+    inv_delta = delta > 0.0f ? 1.0f / delta : 0.0f;
+    zeta = delta > 0.0f ? -rintf(lo / delta) : 0.0f;
+  } else {
+    delta = amax / qmax;
+    inv_delta = amax > 0.0f ? 1.0f / delta : 0.0f;
+  }
   float sse = 0.0f, en = 0.0f;
   auto score = [&](const uint4& v) {
     float f[EPC];
     expand(v, f);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) {
-      const float code = fminf(fmaxf(rintf(f[e] * inv_delta), -qmax), qmax);
-      const float err = fmaf(-delta, code, f[e]);
+      float err;
+      if constexpr (ZP) {
+        const float code = fminf(fmaxf(rintf(f[e] * inv_delta) + zeta, 0.0f), qmax);
+        // a constant row (delta = 0) has the single level lo
+        err = delta > 0.0f ? fmaf(-delta, code - zeta, f[e]) : f[e] - lo;
+      } else {
+        const float code = fminf(fmaxf(rintf(f[e] * inv_delta), -qmax), qmax);
+        err = fmaf(-delta, code, f[e]);
+      }
       sse = fmaf(err, err, sse);
       en = fmaf(f[e], f[e], en);
     }
@@ -569,14 +601,18 @@ hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, float* row_sse,
-                              float* row_en, double* out, hipStream_t s) {
-  const float qmax = (float)((1 << (bits - 1)) - 1);
+hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
+                              float* row_sse, float* row_en, double* out, hipStream_t s) {
+  const float qmax = zero_point ? (float)((1 << bits) - 1) : (float)((1 << (bits - 1)) - 1);
   const dim3 grid((unsigned)T);
-  if (y_is_f32)
-    hipLaunchKernelGGL(k_quant_error<true>, grid, dim3(256), 0, s, Y, T, ld, d, qmax, row_sse, row_en);
+  if (y_is_f32 && zero_point)
+    hipLaunchKernelGGL((k_quant_error<true, true>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
+  else if (y_is_f32)
+    hipLaunchKernelGGL((k_quant_error<true, false>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
+  else if (zero_point)
+    hipLaunchKernelGGL((k_quant_error<false, true>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
   else
-    hipLaunchKernelGGL(k_quant_error<false>, grid, dim3(256), 0, s, Y, T, ld, d, qmax, row_sse, row_en);
+    hipLaunchKernelGGL((k_quant_error<false, false>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(1024), 0, s, row_sse, row_en, T, out);

@@ -83,6 +83,10 @@ def test_full_batch_elementwise(B, name):
         sg, eg = cal.quant_error(Xd, 4)
         say(f"  {name}: int4 SSE gpu={sg:.6e} oracle={so:.6e}  energy gpu={eg:.6e} oracle={eo:.6e}")
         assert abs(sg - so) <= 1e-3 * so and abs(eg - eo) <= 1e-3 * eo
+        so, eo, _, _ = oc.quant_error_zp(X, 4, 0.9)
+        sg, eg = cal.quant_error_zp(Xd, 4, 0.9)
+        say(f"  {name}: zero-point int4 (clip 0.9) SSE gpu={sg:.6e} oracle={so:.6e}")
+        assert abs(sg - so) <= 1e-3 * so and abs(eg - eo) <= 1e-3 * eo
         # Procrustes from the oracle's M, checked by the polar factor's defining properties
         M = oc.M[0]
         cal.set_state(M=M.astype(np.float32))

@@ -110,10 +110,18 @@ def compare_update(B, cal, oc, w, tag, check_R):
 
 def compare_quant(B, cal, oc, X, w, tag):
     sse_o, en_o, _, _ = oc.quant_error(X, 4)
-    sse_g, en_g = cal.quant_error(B.to_device(X, w.dtype), 4)
+    Xd = B.to_device(X, w.dtype)
+    sse_g, en_g = cal.quant_error(Xd, 4)
     say(f"  {tag}: int4 rel.err gpu={sse_g / en_g:.6e} oracle={sse_o / en_o:.6e}")
     assert abs(sse_g - sse_o) <= TOL_REL * sse_o
     assert abs(en_g - en_o) <= TOL_REL * en_o
+    # the zero-point quantiser, at the appendix's definition and at the evaluation clipping ratio
+    for clip in (1.0, 0.9):
+        so, eo, _, _ = oc.quant_error_zp(X, 4, clip)
+        sg, eg = cal.quant_error_zp(Xd, 4, clip)
+        say(f"  {tag}: zero-point int4 clip {clip}: rel.err gpu={sg / eg:.6e} oracle={so / eo:.6e}")
+        assert abs(sg - so) <= TOL_REL * so + 1e-30
+        assert abs(eg - eo) <= TOL_REL * eo
 
 
 def run_stream(B, w, n_batches, check_R, tokens=None, **cal_kwargs):
@@ -339,6 +347,43 @@ def test_quant_error_closed_forms(B):
         s4, e4 = cal.quant_error(Xr, 4)
         s8, e8 = cal.quant_error(Xr, 8)
         assert e4 == e8 and s8 < s4 / 20
+    finally:
+        cal.close()
+
+
+def test_zero_point_quantiser_closed_forms(B):
+    """Rows on the unsigned grid (any zero point) have zero error; hand-computed rows; bits 2..8; constant rows."""
+    import torch
+    d = 64
+    cal = B.Calibrator(d, 1, "f32", np.eye(d, dtype=np.float32), max_tokens=64)
+    try:
+        g = np.random.Generator(np.random.Philox(key=31))
+        codes = g.integers(0, 16, size=(8, d)).astype(np.float64)
+        codes[:, 0] = 0; codes[:, 1] = 15
+        for zeta in (0, 5, 15, -3):
+            Y = ((codes - zeta) * 0.25).astype(np.float32)
+            sse, en = cal.quant_error_zp(B.to_device(Y, "f32"), 4, 1.0)
+            assert sse == 0.0 and np.isclose(en, (Y.astype(np.float64) ** 2).sum())
+        # half-integers on a unit grid 0..15: each odd half is off by 1/2
+        halves = g.integers(0, 31, size=(8, d)) * 0.5
+        halves[:, 0] = 0.0; halves[:, 1] = 15.0
+        sse, _ = cal.quant_error_zp(B.to_device(halves.astype(np.float32), "f32"), 4, 1.0)
+        assert np.isclose(sse, 0.25 * (np.round(halves * 2) % 2 == 1).sum(), rtol=1e-6)
+        # clip 0.75 on -2..2 at 2 bits (tiled to the row width): codes 0,1,2,3,3 -> SSE 1 per group of five
+        row = np.tile(np.array([-2.0, -1.0, 0.0, 1.0, 2.0], dtype=np.float32), 13)[:d]
+        sse, _ = cal.quant_error_zp(B.to_device(row[None, :].copy(), "f32"), 2, 0.75)
+        assert np.isclose(sse, float((row == 2.0).sum()), rtol=1e-6)
+        # constant and zero rows
+        sse, en = cal.quant_error_zp(B.to_device(np.stack([np.full(d, 2.5, np.float32), np.zeros(d, np.float32)]), "f32"), 4, 1.0)
+        assert sse == 0.0 and np.isclose(en, d * 6.25)
+        # more bits, less error; invalid clip ratio is rejected
+        Yr = g.standard_normal((32, d)).astype(np.float32)
+        errs = [cal.quant_error_zp(B.to_device(Yr, "f32"), b, 1.0)[0] for b in (2, 4, 8)]
+        assert errs[0] > 10 * errs[1] > 100 * errs[2] > 0
+        for bad in (0.0, 1.5, float("nan")):
+            with pytest.raises(B.ConqurError) as e:
+                cal.quant_error_zp(B.to_device(Yr, "f32"), 4, bad)
+            assert e.value.status == B.EINVAL
     finally:
         cal.close()
 
