@@ -31,7 +31,8 @@ constexpr int kResidSlots = 512;
 // operands, fp32 iterate): used where the residual is predicted instead of measured.
 constexpr double kOrthFloorPerDim = 1e-8;
 constexpr double kCubeFactor = 5.5;
-constexpr int kClkMaxWorkgroups = 8192;   // clock probes are taken for GEMM launches of at most this many workgroups
+constexpr int kClkMaxWorkgroups = 8192;
+constexpr int64_t kHostSumRows = 16384;   // quant_error: up to this many rows the host adds the per-row results   // clock probes are taken for GEMM launches of at most this many workgroups
 
 enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_STEP, ST_QUANT, ST_COUNT };
 constexpr int kTimingSlots = 12;
@@ -230,8 +231,8 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   ctx->l_base.assign(ctx->heads, 0.0);
   A(dev_alloc(ctx, &ctx->nonfinite, (size_t)4));
   A(dev_alloc(ctx, reinterpret_cast<char**>(&ctx->Y), tmax * d * (ctx->f32 ? 4 : 2)));
-  A(dev_alloc(ctx, &ctx->row_sse, tmax));
-  A(dev_alloc(ctx, &ctx->row_en, tmax));
+  A(dev_alloc(ctx, &ctx->row_sse, 2 * tmax));   // per-row SSE, then per-row energy
+  ctx->row_en = ctx->row_sse + tmax;
   A(dev_alloc(ctx, &ctx->qsum, (size_t)2));
   A(dev_alloc(ctx, &ctx->PX, blk));
   for (int b = 0; b < 2; ++b) {
@@ -748,13 +749,22 @@ static conqur_status quant_error_impl(conqur_ctx* ctx, const void* X, uint64_t T
   }
   {
     StageTimer tm(ctx, ST_QERR);
+    // a batch's per-row results are small: the host adds them (fixed order) instead of one more kernel launch
     HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, zero_point, clip, ctx->row_sse, ctx->row_en,
-                               ctx->qsum, s));
+                               T <= kHostSumRows ? nullptr : ctx->qsum, s));
   }
   }
   double host[2] = {0.0, 0.0};
-  HIP_TRY(hipMemcpyAsync(host, ctx->qsum, sizeof(host), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
+  if (T <= kHostSumRows) {
+    std::vector<float> rows((size_t)2 * T);
+    HIP_TRY(hipMemcpy2DAsync(rows.data(), T * sizeof(float), ctx->row_sse, ctx->tmax * sizeof(float), T * sizeof(float), 2,
+                             hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    for (int64_t i = 0; i < T; ++i) { host[0] += (double)rows[i]; host[1] += (double)rows[T + i]; }
+  } else {
+    HIP_TRY(hipMemcpyAsync(host, ctx->qsum, sizeof(host), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+  }
   *sse = host[0];
   *energy = host[1];
   return CONQUR_OK;

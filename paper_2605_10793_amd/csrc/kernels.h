@@ -80,7 +80,7 @@ hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int 
                                 bf16_bits* Pn, bf16_bits* Pt, int64_t plane, hipStream_t s);
 
 // Per-row fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse / row_en, then their sums over rows:
-// out[0] = SSE, out[1] = energy.  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
+// out[0] = SSE, out[1] = energy (skipped if out is null).  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
 hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
                               float* row_sse, float* row_en, double* out, hipStream_t s);
 

@@ -614,7 +614,7 @@ hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld
   else
     hipLaunchKernelGGL((k_quant_error<false, false>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !out) return e;   // out == null: the caller sums the per-row results itself
   hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(1024), 0, s, row_sse, row_en, T, out);
   return hipGetLastError();
 }

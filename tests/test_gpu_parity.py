@@ -351,6 +351,19 @@ def test_quant_error_closed_forms(B):
         cal.close()
 
 
+def test_quant_error_many_rows(B):
+    """More rows than the host-side summation handles: the on-device sum of the per-row results."""
+    w = I.small_workload(64, 20000, n_batches=1, seed=17)
+    X = I.batch(w, 0)
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(64, 1, "bf16", R0)
+    cal = B.Calibrator(64, 1, "bf16", R0, max_tokens=20000)
+    try:
+        compare_quant(B, cal, oc, X, w, "20000 rows")
+    finally:
+        cal.close()
+
+
 def test_zero_point_quantiser_closed_forms(B):
     """Rows on the unsigned grid (any zero point) have zero error; hand-computed rows; bits 2..8; constant rows."""
     import torch
