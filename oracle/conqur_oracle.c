@@ -457,3 +457,50 @@ int oq_quant_error_zp(const float* X, uint64_t T, uint64_t d, uint64_t heads, ui
   free(rs); free(re);
   return 0;
 }
+
+/*
+ * Per-row diagnostics of the rotated activations (Sec. 4.2 and App. B):
+ *   y as in oq_quant_error (x R_op per head, stored in the activation dtype), whole row of width d;
+ *   pr[i]  = PR(y)/d = ||y||_2^4 / (d ||y||_4^4)          in [1/d, 1]   (normalised participation ratio)
+ *   rho[i] = ||y||_inf^2 / ||y||_2^2                       in [1/d, 1]   (dynamic-range ratio of the SQNR bound)
+ * A row with zero or non-finite energy gets pr = rho = 0.  All arithmetic in fp64.
+ */
+int oq_row_diagnostics(const float* X, uint64_t T, uint64_t d, uint64_t heads, uint64_t row_stride,
+                       const float* R_op, int dtype, double* pr, double* rho) {
+  if (!X || !R_op || heads == 0 || d % heads || row_stride < d) return -1;
+  const uint64_t dh = d / heads;
+#pragma omp parallel
+  {
+    double* y = (double*)malloc(sizeof(double) * d);
+#pragma omp for schedule(static)
+    for (uint64_t i = 0; i < T; ++i) {
+      for (uint64_t h = 0; h < heads; ++h) {
+        const float* x = X + i * row_stride + h * dh;
+        const float* Rh = R_op + h * dh * dh;
+        double* yh = y + h * dh;
+        for (uint64_t j = 0; j < dh; ++j) yh[j] = 0.0;
+        for (uint64_t k = 0; k < dh; ++k) {
+          const double xik = (double)x[k];
+          for (uint64_t j = 0; j < dh; ++j) yh[j] += xik * (double)Rh[k * dh + j];
+        }
+      }
+      double s2 = 0.0, s4 = 0.0, mx = 0.0;
+      for (uint64_t j = 0; j < d; ++j) {
+        y[j] = dtype == 1 ? oq_round_bf16_f64(y[j]) : (double)(float)y[j];
+        const double a = fabs(y[j]);
+        if (a > mx) mx = a;
+      }
+      /* scaled by the row maximum so that fourth powers neither overflow nor vanish */
+      for (uint64_t j = 0; j < d; ++j) {
+        const double u = mx > 0.0 ? y[j] / mx : 0.0;
+        s2 += u * u;
+        s4 += u * u * u * u;
+      }
+      const int ok = mx > 0.0 && isfinite(mx) && isfinite(s2);
+      if (pr) pr[i] = ok ? s2 * s2 / ((double)d * s4) : 0.0;
+      if (rho) rho[i] = ok ? 1.0 / s2 : 0.0;
+    }
+    free(y);
+  }
+  return 0;
+}

@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.oq_procrustes.argtypes = [p, p, u64, dbl, p, p]
         L.oq_quant_error.restype = i32
         L.oq_quant_error.argtypes = [p, u64, u64, u64, u64, p, i32, i32, p, p, p, p]
+        L.oq_row_diagnostics.restype = i32
+        L.oq_row_diagnostics.argtypes = [p, u64, u64, u64, u64, p, i32, p, p]
         L.oq_quant_error_zp.restype = i32
         L.oq_quant_error_zp.argtypes = [p, u64, u64, u64, u64, p, i32, i32, ctypes.c_float, p, p, p, p]
         _lib = L
@@ -160,6 +162,17 @@ class OracleCalibrator:
         if rc != 0:
             raise RuntimeError("oq_quant_error failed")
         return sse.value, en.value, rows, codes
+
+    def row_diagnostics(self, X: np.ndarray):
+        """Per row of Y = X R_op: normalised participation ratio PR/d (Sec. 4.2) and ||y||_inf^2/||y||_2^2 (App. B)."""
+        X = np.ascontiguousarray(X, dtype=np.float32)
+        T, stride = X.shape
+        pr = np.empty(T, dtype=np.float64); rho = np.empty(T, dtype=np.float64)
+        rc = lib().oq_row_diagnostics(_ptr(X), T, self.d, self.heads, stride, _ptr(self.R_op),
+                                      1 if self.dtype == "bf16" else 0, _ptr(pr), _ptr(rho))
+        if rc != 0:
+            raise RuntimeError("oq_row_diagnostics failed")
+        return pr, rho
 
     def quant_error_zp(self, X: np.ndarray, bits: int = 4, clip: float = 1.0, want_rows: bool = False,
                        want_codes: bool = False):

@@ -490,3 +490,62 @@ def test_zeropoint_bounds_from_appendix_b(golden):
     upper = (inside * (dc / 2) ** 2 + (~inside) * (over + dc / 2) ** 2).sum(axis=1)
     assert np.all(rows_c <= upper * (1 + 1e-5) + 1e-12)
     assert np.all(rows_c >= (over ** 2 * 0.99).sum(axis=1) - 1e-9 - (2 * over * dc / 2).sum(axis=1))
+
+
+# --------------------------------------------------------------------------- diagnostics (Sec. 4.2, App. B)
+
+def test_participation_ratio_closed_forms(golden):
+    d = 64
+    oc = O.OracleCalibrator(d, 1, "f32", np.eye(d, dtype=np.float32))
+    rows = np.zeros((6, d), dtype=np.float32)
+    rows[0, 17] = -3.0                                   # one-sparse: PR/d = 1/d, rho = 1
+    rows[1] = np.where(np.arange(d) % 3 == 0, -0.5, 0.5)  # equal magnitude: PR/d = 1, rho = 1/d
+    rows[2, :8] = [2, -2, 2, 2, -2, 2, -2, -2]           # k-sparse with equal magnitudes: PR/d = k/d, rho = 1/k
+    rows[3, 0], rows[3, 1] = 1.0, 3.0                    # (1 + 9)^2 / (1 + 81) = 100/82; rho = 9/10
+    rows[4] = 1e15 * rows[1]                             # fourth powers beyond fp32 and near fp64 limits still fine
+    pr, rho = oc.row_diagnostics(rows)
+    assert np.isclose(pr[0] * d, golden["pr_one_sparse_times_d"], rtol=1e-12) and np.isclose(rho[0], 1.0)
+    assert np.isclose(pr[1], golden["pr_equal_magnitude"], rtol=1e-12) and np.isclose(rho[1], 1.0 / d)
+    assert np.isclose(pr[2], 8.0 / d, rtol=1e-12) and np.isclose(rho[2], 1.0 / 8)
+    assert np.isclose(pr[3], 100.0 / 82.0 / d, rtol=1e-12) and np.isclose(rho[3], 0.9)
+    assert np.isclose(pr[4], 1.0, rtol=1e-6) and np.isclose(rho[4], 1.0 / d, rtol=1e-6)
+    assert pr[5] == 0.0 and rho[5] == 0.0                # zero row
+
+
+def test_participation_ratio_invariants_and_gaussian_value():
+    """1/d <= PR/d <= 1, 1/d <= rho <= 1, PR >= 1/rho (||y||_4^4 <= ||y||_inf^2 ||y||_2^2); scale and permutation
+    invariance; rotation and heads are applied; Gaussian rows have PR/d near 1/3 (E y^4 = 3 sigma^4), the level the
+    paper reports for random Hadamard mixing."""
+    d = 512
+    w = I.small_workload(d, 200, seed=23)
+    X = I.batch(w, 0)
+    R = I.initial_rotation(w)
+    oc = O.OracleCalibrator(d, 1, "bf16", R)
+    pr, rho = oc.row_diagnostics(X)
+    assert np.all(pr >= 1.0 / d - 1e-12) and np.all(pr <= 1.0 + 1e-12)
+    assert np.all(rho >= 1.0 / d - 1e-12) and np.all(rho <= 1.0 + 1e-12)
+    assert np.all(pr * d >= 1.0 / rho * (1 - 1e-12))
+    Y = I.round_to_bf16((X.astype(np.float64) @ oc.R_op[0].astype(np.float64)).astype(np.float32)).astype(np.float64)
+    assert np.allclose(pr, (Y ** 2).sum(1) ** 2 / (d * (Y ** 4).sum(1)), rtol=1e-10)      # direct definition
+    assert np.allclose(rho, np.abs(Y).max(1) ** 2 / (Y ** 2).sum(1), rtol=1e-10)
+    ident = O.OracleCalibrator(d, 1, "f32", np.eye(d, dtype=np.float32))
+    Xf = X.astype(np.float32)
+    p0, r0 = ident.row_diagnostics(Xf)
+    p1, r1 = ident.row_diagnostics(Xf * 4.0)
+    perm = np.random.Generator(np.random.Philox(key=3)).permutation(d)
+    p2, r2 = ident.row_diagnostics(np.ascontiguousarray(Xf[:, perm]))
+    assert np.array_equal(p0, p1) and np.array_equal(r0, r1)
+    assert np.allclose(p0, p2, rtol=1e-12) and np.allclose(r0, r2, rtol=1e-12)
+    # rotating the outlier-heavy rows spreads their energy: PR goes up
+    assert pr.mean() > 3 * p0.mean()
+    G = np.random.Generator(np.random.Philox(key=4)).standard_normal((400, 4096)).astype(np.float32)
+    pg, _ = O.OracleCalibrator(4096, 1, "f32", np.eye(4096, dtype=np.float32)).row_diagnostics(G)
+    assert abs(pg.mean() - 1.0 / 3.0) < 0.01
+    # two heads: each half rotated by its own block
+    w2 = I.small_workload(32, 20, heads=2, seed=24)
+    X2 = I.batch(w2, 0)
+    oc2 = O.OracleCalibrator(32, 2, "f32", I.initial_rotation(w2))
+    pr2, _ = oc2.row_diagnostics(X2)
+    Rop = oc2.R_op.astype(np.float64)
+    Y2 = np.concatenate([X2[:, :16].astype(np.float64) @ Rop[0], X2[:, 16:].astype(np.float64) @ Rop[1]], axis=1).astype(np.float32).astype(np.float64)
+    assert np.allclose(pr2, (Y2 ** 2).sum(1) ** 2 / (32 * (Y2 ** 4).sum(1)), rtol=1e-9)
