@@ -92,6 +92,7 @@ def main():
     R0 = I.initial_rotation(w)
     dev = [B.to_device(x, w.dtype) for x in host]
     cal = B.Calibrator(d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
+    pr_start = float(cal.row_diagnostics(dev[0])[0].mean())      # mean PR/d of batch 0 under the initial rotation
     cal.set_timing(1)               # one event pair around each whole call
 
     def one_step(i):
@@ -170,6 +171,7 @@ def main():
         "stage_ms": acc,
         "stage_ms_note": "second pass of the same steps with an event pair around every kernel stage",
         "int4_rel_err_first_last": [rel[0], rel[-1]],
+        "mean_participation_ratio_first_last": [pr_start, float(cal.row_diagnostics(dev[0])[0].mean())],
         "roofline": {
             "bound": "mfma", "kernel": "gemm_nt_kernel (rotate+corner launch and accumulate launch of step_batch)",
             "achieved": step_flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -152,6 +152,18 @@ conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X_dev, uint64_t
                                     uint32_t bits, float clip_ratio, double* sse_host, double* energy_host);
 
 /*
+ * Per-row diagnostics of the rotated activations: Y = X R_op per head, stored in
+ * act_dtype, then per token over the whole row of width d
+ *   pr  = ||y||_2^4 / (d ||y||_4^4)   normalised participation ratio (Sec. 4.2), in [1/d, 1]
+ *   rho = ||y||_inf^2 / ||y||_2^2     dynamic-range ratio of the SQNR bound (App. B), in [1/d, 1]
+ * pr_host / rho_host: HOST, T floats each, either may be NULL; a row with zero or
+ * non-finite energy gets 0.  X_dev as in conqur_step_batch.  Does not change the
+ * calibration state.  Synchronises the stream.
+ */
+conqur_status conqur_row_diagnostics(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems,
+                                     float* pr_host, float* rho_host);
+
+/*
  * Copy state to the host / replace it (checkpointing, and teacher-forced parity
  * tests).  R_host, M_host: HOST, heads*dh*dh floats or NULL.  n_rows_host: HOST,
  * `heads` entries or NULL.  set_state(R) also refreshes the rotate operand;

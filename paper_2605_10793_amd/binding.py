@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
-    "conqur_quant_error", "conqur_quant_error_zp", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
+    "conqur_quant_error", "conqur_quant_error_zp", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
     "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
         L.conqur_quant_error_zp.restype = i32
         L.conqur_quant_error_zp.argtypes = [vp, vp, u64, u64, u32, ctypes.c_float, ctypes.POINTER(ctypes.c_double),
                                             ctypes.POINTER(ctypes.c_double)]
+        L.conqur_row_diagnostics.restype = i32
+        L.conqur_row_diagnostics.argtypes = [vp, vp, u64, u64, vp, vp]
         L.conqur_get_state.restype = i32
         L.conqur_get_state.argtypes = [vp, vp, vp, vp]
         L.conqur_set_state.restype = i32
@@ -179,6 +181,13 @@ class Calibrator:
         self._check(self._lib.conqur_quant_error_zp(self._h, p, T, stride, bits, ctypes.c_float(clip_ratio),
                                                     ctypes.byref(sse), ctypes.byref(en)))
         return sse.value, en.value
+
+    def row_diagnostics(self, X):
+        """Per row of Y = X R_op: (PR/d, ||y||_inf^2/||y||_2^2) as two float32 arrays of length T."""
+        p, T, stride = self._x(X)
+        pr = np.empty(T, dtype=np.float32); rho = np.empty(T, dtype=np.float32)
+        self._check(self._lib.conqur_row_diagnostics(self._h, p, T, stride, _np_ptr(pr), _np_ptr(rho)))
+        return pr, rho
 
     def get_state(self, want_R: bool = True, want_M: bool = True):
         shape = (self.heads, self.dh, self.dh)

@@ -780,6 +780,26 @@ conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X, uint64_t T, 
   return quant_error_impl(ctx, X, T, stride, bits, 1, clip_ratio, sse, energy);
 }
 
+conqur_status conqur_row_diagnostics(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, float* pr_host,
+                                     float* rho_host) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+  hipStream_t s = ctx->stream;
+  if (ctx->f32)
+    HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
+  GemmArgs g;
+  rotate_args(ctx, X, T, stride, &g);
+  g.C = ctx->Y; g.ldc = ctx->d; g.batchC = ctx->dh; g.c_is_f32 = ctx->f32;
+  HIP_TRY(launch_gemm_nt(g, EPI_ACT, ctx->heads, s));
+  HIP_TRY(launch_row_diag(ctx->Y, ctx->f32, T, ctx->d, ctx->d, ctx->row_sse, ctx->row_en, s));
+  if (pr_host) HIP_TRY(hipMemcpyAsync(pr_host, ctx->row_sse, T * sizeof(float), hipMemcpyDeviceToHost, s));
+  if (rho_host) HIP_TRY(hipMemcpyAsync(rho_host, ctx->row_en, T * sizeof(float), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return CONQUR_OK;
+}
+
 conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, uint64_t* n_rows) {
   if (!ctx) return CONQUR_EINVAL;
   const size_t blk = (size_t)ctx->heads * ctx->dh * ctx->dh;

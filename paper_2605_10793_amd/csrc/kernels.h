@@ -84,6 +84,11 @@ hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int 
 hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
                               float* row_sse, float* row_en, double* out, hipStream_t s);
 
+// Per-row diagnostics of Y [T][ld] (bf16 or fp32): row_pr = ||y||_2^4 / (d ||y||_4^4), row_rho = ||y||_inf^2 / ||y||_2^2
+// (0, 0 for a row with zero or non-finite energy).
+hipError_t launch_row_diag(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, float* row_pr, float* row_rho,
+                           hipStream_t s);
+
 // out[h] = sum of part[h][0..n) for h < heads, fixed order.
 hipError_t launch_sum_partials(const double* part, int n, int heads, double* out, hipStream_t s);
 

@@ -464,6 +464,78 @@ __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y,
   }
 }
 
+// ---------------------------------------------------------------- row diagnostics
+// One workgroup per row of Y, same single pass as k_quant_error (row cached in registers): pr = ||y||_2^4 / (d ||y||_4^4)
+// (normalised participation ratio, Sec. 4.2) and rho = ||y||_inf^2 / ||y||_2^2 (App. B).  The sums run over u = y / max|y|,
+// so that fourth powers neither overflow nor vanish; a row with zero or non-finite energy gets 0, 0.
+template <bool F32>
+__global__ void __launch_bounds__(256) k_row_diag(const void* __restrict__ Y, int64_t T, int64_t ld, int d,
+                                                  float* __restrict__ row_pr, float* __restrict__ row_rho) {
+  constexpr int EPC = F32 ? 4 : 8;
+  constexpr int NC = 4;
+  __shared__ float shm[4], sh2[4], sh4[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = blockIdx.x;
+  const int nch = d / EPC;
+  auto expand = [](const uint4& v, float* f) {
+    if constexpr (F32) {
+      f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    } else {
+      unpack8(v, f);
+    }
+  };
+  const uint4* y = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(Y) + row * ld * (F32 ? 4 : 2));
+  uint4 cache[NC];
+  float amax = 0.0f;
+  auto track = [&](const uint4& v) {
+    float f[EPC];
+    expand(v, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) amax = fmaxf(amax, fabsf(f[e]));   // fmaxf drops NaN: caught through the sums below
+  };
+#pragma unroll
+  for (int q = 0; q < NC; ++q) {
+    const int c = threadIdx.x + 256 * q;
+    cache[q] = make_uint4(0, 0, 0, 0);
+    if (c < nch) {
+      cache[q] = y[c];
+      track(cache[q]);
+    }
+  }
+  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) track(y[c]);
+  amax = wave_max(amax);
+  if (lane == 0) shm[wave] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(shm[0], shm[1]), fmaxf(shm[2], shm[3]));
+  const float inv = (amax > 0.0f && isfinite(amax)) ? 1.0f / amax : 0.0f;
+  float s2 = 0.0f, s4 = 0.0f;
+  auto score = [&](const uint4& v) {
+    float f[EPC];
+    expand(v, f);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      const float u = f[e] * inv, u2 = u * u;
+      s2 += u2;
+      s4 = fmaf(u2, u2, s4);
+    }
+  };
+#pragma unroll
+  for (int q = 0; q < NC; ++q)
+    if ((int)threadIdx.x + 256 * q < nch) score(cache[q]);
+  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) score(y[c]);
+  s2 = wave_sum(s2);
+  s4 = wave_sum(s4);
+  if (lane == 0) { sh2[wave] = s2; sh4[wave] = s4; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const double t2 = (double)sh2[0] + (double)sh2[1] + (double)sh2[2] + (double)sh2[3];
+    const double t4 = (double)sh4[0] + (double)sh4[1] + (double)sh4[2] + (double)sh4[3];
+    const bool ok = inv > 0.0f && t2 > 0.0 && isfinite(t2) && t4 > 0.0;
+    row_pr[row] = ok ? (float)(t2 * t2 / ((double)d * t4)) : 0.0f;
+    row_rho[row] = ok ? (float)(1.0 / t2) : 0.0f;
+  }
+}
+
 // out[0] = sum a, out[1] = sum b in a fixed order (one workgroup).  Results of many
 // workgroups are combined this way rather than with atomics on one address, which the
 // XCDs would serialise at the memory side.
@@ -616,6 +688,16 @@ hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !out) return e;   // out == null: the caller sums the per-row results itself
   hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(1024), 0, s, row_sse, row_en, T, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_diag(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, float* row_pr, float* row_rho,
+                           hipStream_t s) {
+  const dim3 grid((unsigned)T);
+  if (y_is_f32)
+    hipLaunchKernelGGL(k_row_diag<true>, grid, dim3(256), 0, s, Y, T, ld, d, row_pr, row_rho);
+  else
+    hipLaunchKernelGGL(k_row_diag<false>, grid, dim3(256), 0, s, Y, T, ld, d, row_pr, row_rho);
   return hipGetLastError();
 }
 

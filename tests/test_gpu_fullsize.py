@@ -83,6 +83,10 @@ def test_full_batch_elementwise(B, name):
         sg, eg = cal.quant_error(Xd, 4)
         say(f"  {name}: int4 SSE gpu={sg:.6e} oracle={so:.6e}  energy gpu={eg:.6e} oracle={eo:.6e}")
         assert abs(sg - so) <= 1e-3 * so and abs(eg - eo) <= 1e-3 * eo
+        pr_o, rho_o = oc.row_diagnostics(X)
+        pr_g, rho_g = cal.row_diagnostics(Xd)
+        say(f"  {name}: mean PR/d gpu={pr_g.mean():.6f} oracle={pr_o.mean():.6f}; mean rho gpu={rho_g.mean():.6e} oracle={rho_o.mean():.6e}")
+        assert np.allclose(pr_g, pr_o, rtol=1e-3, atol=1e-7) and np.allclose(rho_g, rho_o, rtol=1e-3, atol=1e-7)
         so, eo, _, _ = oc.quant_error_zp(X, 4, 0.9)
         sg, eg = cal.quant_error_zp(Xd, 4, 0.9)
         say(f"  {name}: zero-point int4 (clip 0.9) SSE gpu={sg:.6e} oracle={so:.6e}")

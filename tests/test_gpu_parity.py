@@ -115,6 +115,10 @@ def compare_quant(B, cal, oc, X, w, tag):
     say(f"  {tag}: int4 rel.err gpu={sse_g / en_g:.6e} oracle={sse_o / en_o:.6e}")
     assert abs(sse_g - sse_o) <= TOL_REL * sse_o
     assert abs(en_g - en_o) <= TOL_REL * en_o
+    # per-row diagnostics (participation ratio, range ratio)
+    pr_o, rho_o = oc.row_diagnostics(X)
+    pr_g, rho_g = cal.row_diagnostics(Xd)
+    assert np.allclose(pr_g, pr_o, rtol=1e-3, atol=1e-7) and np.allclose(rho_g, rho_o, rtol=1e-3, atol=1e-7), tag
     # the zero-point quantiser, at the appendix's definition and at the evaluation clipping ratio
     for clip in (1.0, 0.9):
         so, eo, _, _ = oc.quant_error_zp(X, 4, clip)
@@ -347,6 +351,28 @@ def test_quant_error_closed_forms(B):
         s4, e4 = cal.quant_error(Xr, 4)
         s8, e8 = cal.quant_error(Xr, 8)
         assert e4 == e8 and s8 < s4 / 20
+    finally:
+        cal.close()
+
+
+def test_row_diagnostics_closed_forms(B):
+    d = 64
+    cal = B.Calibrator(d, 1, "f32", np.eye(d, dtype=np.float32), max_tokens=16)
+    try:
+        rows = np.zeros((7, d), dtype=np.float32)
+        rows[0, 17] = -3.0                                     # one-sparse
+        rows[1] = np.where(np.arange(d) % 3 == 0, -0.5, 0.5)    # equal magnitude
+        rows[2, :8] = [2, -2, 2, 2, -2, 2, -2, -2]             # 8-sparse, equal magnitudes
+        rows[3, 0], rows[3, 1] = 1.0, 3.0
+        rows[4] = 1e15 * rows[1]                               # fourth powers overflow fp32 without the scaling
+        rows[5] = 1e-15 * rows[1]
+        pr, rho = cal.row_diagnostics(B.to_device(rows, "f32"))
+        assert np.allclose(pr[:6], [1 / d, 1.0, 8 / d, 100 / 82 / d, 1.0, 1.0], rtol=1e-6)
+        assert np.allclose(rho[:6], [1.0, 1 / d, 1 / 8, 0.9, 1 / d, 1 / d], rtol=1e-6)
+        assert pr[6] == 0.0 and rho[6] == 0.0
+        rows[2, 3] = np.nan
+        pr, rho = cal.row_diagnostics(B.to_device(rows, "f32"))
+        assert pr[2] == 0.0 and rho[2] == 0.0 and np.isclose(pr[1], 1.0, rtol=1e-6)
     finally:
         cal.close()
 
