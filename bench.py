@@ -29,8 +29,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16/fp16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per step_batch GEMM launch pair on c3, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes scaled by a
-# 256 MiB copy (profiles/bench_c3_pmc_traffic_mfma.txt): fetch 224.5 MiB + write 81.3 MiB.
-MEASURED_TRAFFIC_BYTES = {"c3": 3.21e8}
+# 256 MiB copy (profiles/bench_c3_pmc_traffic_mfma.txt): fetch 224.4 MiB + write 80.0 MiB.
+MEASURED_TRAFFIC_BYTES = {"c3": 3.19e8}
 
 
 def cpu_baseline(w, X0, R0, sample_tokens):

@@ -757,8 +757,8 @@ static conqur_status quant_error_impl(conqur_ctx* ctx, const void* X, uint64_t T
   double host[2] = {0.0, 0.0};
   if (T <= kHostSumRows) {
     std::vector<float> rows((size_t)2 * T);
-    HIP_TRY(hipMemcpy2DAsync(rows.data(), T * sizeof(float), ctx->row_sse, ctx->tmax * sizeof(float), T * sizeof(float), 2,
-                             hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(rows.data(), ctx->row_sse, T * sizeof(float), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(rows.data() + T, ctx->row_en, T * sizeof(float), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     for (int64_t i = 0; i < T; ++i) { host[0] += (double)rows[i]; host[1] += (double)rows[T + i]; }
   } else {
@@ -858,24 +858,24 @@ conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs, float* nor
   if (ctx->last_T == 0) return fail(ctx, CONQUR_ESTATE, "no step_batch yet");
   if (signs && !ctx->last_signs_valid)
     return fail(ctx, CONQUR_ESTATE, "the last step did not keep the corner signs: call conqur_set_taps(ctx, 1) before it");
-  const int64_t T = ctx->last_T, d = ctx->d, pitch = ctx->pitch;
+  const int64_t T = ctx->last_T, d = ctx->d, pitch = ctx->pitch, tmax = ctx->tmax;
   hipStream_t s = ctx->stream;
-  std::vector<float> nrm((size_t)ctx->heads * T);
-  HIP_TRY(hipMemcpy2DAsync(nrm.data(), T * sizeof(float), ctx->nrm, ctx->tmax * sizeof(float), T * sizeof(float), ctx->heads,
-                           hipMemcpyDeviceToHost, s));
+  // whole buffers in one plain copy each, sliced on the host (a debug tap: simplicity over bytes moved)
+  std::vector<float> nrm((size_t)ctx->heads * tmax);
+  HIP_TRY(hipMemcpyAsync(nrm.data(), ctx->nrm, nrm.size() * sizeof(float), hipMemcpyDeviceToHost, s));
   std::vector<bf16_bits> st;
   if (signs) {
-    st.resize((size_t)d * T);
-    HIP_TRY(hipMemcpy2DAsync(st.data(), T * sizeof(bf16_bits), ctx->St, pitch * sizeof(bf16_bits), T * sizeof(bf16_bits), d,
-                             hipMemcpyDeviceToHost, s));
+    st.resize((size_t)d * pitch);
+    HIP_TRY(hipMemcpyAsync(st.data(), ctx->St, st.size() * sizeof(bf16_bits), hipMemcpyDeviceToHost, s));
   }
   HIP_TRY(hipStreamSynchronize(s));
-  if (norms) std::memcpy(norms, nrm.data(), nrm.size() * sizeof(float));
+  if (norms)
+    for (int h = 0; h < ctx->heads; ++h) std::memcpy(norms + (size_t)h * T, nrm.data() + (size_t)h * tmax, T * sizeof(float));
   if (signs)
     for (int64_t j = 0; j < d; ++j) {
-      const float* nh = nrm.data() + (j / ctx->dh) * T;
+      const float* nh = nrm.data() + (j / ctx->dh) * tmax;
       for (int64_t i = 0; i < T; ++i)
-        signs[i * d + j] = nh[i] > 0.0f ? ((st[j * T + i] & 0x8000) ? -1 : 1) : 0;
+        signs[i * d + j] = nh[i] > 0.0f ? ((st[j * pitch + i] & 0x8000) ? -1 : 1) : 0;
     }
   return CONQUR_OK;
 }
