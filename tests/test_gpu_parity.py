@@ -276,6 +276,38 @@ def test_rotation_replaced_while_rows_are_pending(B):
         cal.close()
 
 
+def test_several_contexts_interleaved(B):
+    """Alg. 1 keeps one residual-stream rotation and one per-head rotation per layer alive at once: contexts of
+    different shapes, stepped and updated in turn on one stream, do not disturb each other."""
+    specs = [I.small_workload(320, 150, n_batches=2, seed=41, prox_lambda=0.1),
+             I.small_workload(256, 150, n_batches=2, heads=2, seed=42, prox_lambda=0.0),       # two fused heads of width 128
+             I.small_workload(192, 150, n_batches=2, heads=4, seed=43, prox_lambda=0.0)]
+    R0s = [I.initial_rotation(w) for w in specs]
+    def run(order):
+        cals = [B.Calibrator(w.d, w.heads, w.dtype, R0, max_tokens=150, prox_lambda=w.prox_lambda) for w, R0 in zip(specs, R0s)]
+        try:
+            for b in range(2):
+                for k in order:
+                    cals[k].step_batch(B.to_device(I.batch(specs[k], b), specs[k].dtype))
+                for k in reversed(order):
+                    cals[k].update_rotation()
+            return [c.get_state(want_M=False)[0].copy() for c in cals]
+        finally:
+            for c in cals:
+                c.close()
+    together = run([0, 1, 2])
+    for k in range(3):
+        alone_cal = B.Calibrator(specs[k].d, specs[k].heads, specs[k].dtype, R0s[k], max_tokens=150,
+                                 prox_lambda=specs[k].prox_lambda)
+        try:
+            for b in range(2):
+                alone_cal.step_batch(B.to_device(I.batch(specs[k], b), specs[k].dtype))
+                alone_cal.update_rotation()
+            assert np.array_equal(alone_cal.get_state(want_M=False)[0], together[k]), k
+        finally:
+            alone_cal.close()
+
+
 # --------------------------------------------------------------------------- edge cases
 
 def test_zero_and_nonfinite_rows(B):
