@@ -504,3 +504,34 @@ int oq_row_diagnostics(const float* X, uint64_t T, uint64_t d, uint64_t heads, u
   }
   return 0;
 }
+
+/*
+ * The rotated rows themselves: Y = X R_op per head (fp64 accumulation), stored in the
+ * activation dtype (dtype 1: rounded to bf16; dtype 0: rounded to fp32) -- Eq. 1's R x~ before
+ * normalisation, and, with the rows of a weight matrix as X, the folding of the
+ * learned rotation into that matrix (App. A).  Y: T rows of d floats.
+ */
+int oq_rotate(const float* X, uint64_t T, uint64_t d, uint64_t heads, uint64_t row_stride, const float* R_op, int dtype,
+              float* Y) {
+  if (!X || !R_op || !Y || heads == 0 || d % heads || row_stride < d) return -1;
+  const uint64_t dh = d / heads;
+#pragma omp parallel
+  {
+    double* y = (double*)malloc(sizeof(double) * dh);
+#pragma omp for schedule(static)
+    for (uint64_t i = 0; i < T; ++i)
+      for (uint64_t h = 0; h < heads; ++h) {
+        const float* x = X + i * row_stride + h * dh;
+        const float* Rh = R_op + h * dh * dh;
+        for (uint64_t j = 0; j < dh; ++j) y[j] = 0.0;
+        for (uint64_t k = 0; k < dh; ++k) {
+          const double xik = (double)x[k];
+          for (uint64_t j = 0; j < dh; ++j) y[j] += xik * (double)Rh[k * dh + j];
+        }
+        for (uint64_t j = 0; j < dh; ++j)
+          Y[i * d + h * dh + j] = dtype == 1 ? (float)oq_round_bf16_f64(y[j]) : (float)y[j];
+      }
+    free(y);
+  }
+  return 0;
+}

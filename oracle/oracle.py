@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.oq_procrustes.argtypes = [p, p, u64, dbl, p, p]
         L.oq_quant_error.restype = i32
         L.oq_quant_error.argtypes = [p, u64, u64, u64, u64, p, i32, i32, p, p, p, p]
+        L.oq_rotate.restype = i32
+        L.oq_rotate.argtypes = [p, u64, u64, u64, u64, p, i32, p]
         L.oq_row_diagnostics.restype = i32
         L.oq_row_diagnostics.argtypes = [p, u64, u64, u64, u64, p, i32, p, p]
         L.oq_quant_error_zp.restype = i32
@@ -162,6 +164,16 @@ class OracleCalibrator:
         if rc != 0:
             raise RuntimeError("oq_quant_error failed")
         return sse.value, en.value, rows, codes
+
+    def rotate(self, X: np.ndarray) -> np.ndarray:
+        """Y = X R_op per head, stored in the activation dtype (returned as float32)."""
+        X = np.ascontiguousarray(X, dtype=np.float32)
+        T, stride = X.shape
+        Y = np.empty((T, self.d), dtype=np.float32)
+        rc = lib().oq_rotate(_ptr(X), T, self.d, self.heads, stride, _ptr(self.R_op), 1 if self.dtype == "bf16" else 0, _ptr(Y))
+        if rc != 0:
+            raise RuntimeError("oq_rotate failed")
+        return Y
 
     def row_diagnostics(self, X: np.ndarray):
         """Per row of Y = X R_op: normalised participation ratio PR/d (Sec. 4.2) and ||y||_inf^2/||y||_2^2 (App. B)."""

@@ -549,3 +549,34 @@ def test_participation_ratio_invariants_and_gaussian_value():
     Rop = oc2.R_op.astype(np.float64)
     Y2 = np.concatenate([X2[:, :16].astype(np.float64) @ Rop[0], X2[:, 16:].astype(np.float64) @ Rop[1]], axis=1).astype(np.float32).astype(np.float64)
     assert np.allclose(pr2, (Y2 ** 2).sum(1) ** 2 / (32 * (Y2 ** 4).sum(1)), rtol=1e-9)
+
+
+# --------------------------------------------------------------------------- rotate / fold (App. A)
+
+def test_rotate_pins():
+    """Identity, a signed permutation (exact), norm preservation and the round trip (X R) R^T = X for fp32;
+    the bf16 variant is the fp32 one rounded once; heads rotate their own slices."""
+    d = 48
+    g = np.random.Generator(np.random.Philox(key=27))
+    X = g.standard_normal((9, d)).astype(np.float32)
+    assert np.array_equal(O.OracleCalibrator(d, 1, "f32", np.eye(d, dtype=np.float32)).rotate(X), X)
+    perm = g.permutation(d); sgn = np.where(g.random(d) < 0.5, -1.0, 1.0).astype(np.float32)
+    P = np.zeros((d, d), dtype=np.float32); P[perm, np.arange(d)] = sgn            # y_j = sgn_j x_perm[j]
+    assert np.array_equal(O.OracleCalibrator(d, 1, "f32", P).rotate(X), X[:, perm] * sgn)
+    Q = I.random_orthogonal(d, 28).astype(np.float32)
+    oc = O.OracleCalibrator(d, 1, "f32", Q)
+    Y = oc.rotate(X)
+    assert np.allclose(np.linalg.norm(Y, axis=1), np.linalg.norm(X, axis=1), rtol=1e-6)
+    back = O.OracleCalibrator(d, 1, "f32", np.ascontiguousarray(Q.T)).rotate(Y)
+    assert np.allclose(back, X, atol=2e-6)
+    Xb = I.round_to_bf16(X)
+    Yb = O.OracleCalibrator(d, 1, "bf16", Q).rotate(Xb)
+    Qb = I.round_to_bf16(Q)
+    assert np.array_equal(Yb, I.round_to_bf16((Xb.astype(np.float64) @ Qb.astype(np.float64)).astype(np.float32)))
+    R2 = np.stack([I.random_orthogonal(24, 29), I.random_orthogonal(24, 30)]).astype(np.float32)
+    Y2 = O.OracleCalibrator(d, 2, "f32", R2).rotate(X)
+    assert np.allclose(Y2[:, :24], X[:, :24].astype(np.float64) @ R2[0], atol=1e-6)
+    assert np.allclose(Y2[:, 24:], X[:, 24:].astype(np.float64) @ R2[1], atol=1e-6)
+    # the corner signs and the quantiser see exactly these rows
+    _, S = oc.step_batch(X, True, True)
+    assert np.array_equal(S, np.where(Y >= 0, 1, -1))
