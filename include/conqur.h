@@ -152,6 +152,18 @@ conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X_dev, uint64_t
                                     uint32_t bits, float clip_ratio, double* sse_host, double* energy_host);
 
 /*
+ * The rotated rows themselves: Y = X R_op per head (R_op = R rounded to act_dtype;
+ * fp32-equivalent products for fp32), stored in act_dtype -- Eq. 1's R x~ before
+ * normalisation; with the rows of a weight matrix as X this folds the learned rotation
+ * into that matrix (App. A).  X_dev as in conqur_step_batch (T <= max_tokens rows per
+ * call).  Y_dev: DEVICE, T rows of y_row_stride_elems >= d elements of act_dtype, owned
+ * by the caller, must not overlap X.  Asynchronous on the context's stream; does not
+ * change the calibration state.
+ */
+conqur_status conqur_rotate(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems, void* Y_dev,
+                            uint64_t y_row_stride_elems);
+
+/*
  * Per-row diagnostics of the rotated activations: Y = X R_op per head, stored in
  * act_dtype, then per token over the whole row of width d
  *   pr  = ||y||_2^4 / (d ||y||_4^4)   normalised participation ratio (Sec. 4.2), in [1/d, 1]

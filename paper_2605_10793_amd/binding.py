@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
-    "conqur_quant_error", "conqur_quant_error_zp", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
+    "conqur_quant_error", "conqur_quant_error_zp", "conqur_rotate", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
     "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
         L.conqur_quant_error_zp.restype = i32
         L.conqur_quant_error_zp.argtypes = [vp, vp, u64, u64, u32, ctypes.c_float, ctypes.POINTER(ctypes.c_double),
                                             ctypes.POINTER(ctypes.c_double)]
+        L.conqur_rotate.restype = i32
+        L.conqur_rotate.argtypes = [vp, vp, u64, u64, vp, u64]
         L.conqur_row_diagnostics.restype = i32
         L.conqur_row_diagnostics.argtypes = [vp, vp, u64, u64, vp, vp]
         L.conqur_get_state.restype = i32
@@ -181,6 +183,17 @@ class Calibrator:
         self._check(self._lib.conqur_quant_error_zp(self._h, p, T, stride, bits, ctypes.c_float(clip_ratio),
                                                     ctypes.byref(sse), ctypes.byref(en)))
         return sse.value, en.value
+
+    def rotate(self, X, Y=None):
+        """Y = X R_op per head into a device tensor of X's dtype (allocated here unless given); asynchronous."""
+        import torch
+        p, T, stride = self._x(X)
+        if Y is None:
+            Y = torch.empty((T, self.d), dtype=X.dtype, device=X.device)
+        if Y.dtype != X.dtype or Y.dim() != 2 or Y.shape[0] != T or Y.shape[1] < self.d or Y.stride(1) != 1:
+            raise ValueError("Y must be a [T, >= d] tensor of X's dtype with unit column stride")
+        self._check(self._lib.conqur_rotate(self._h, p, T, stride, ctypes.c_void_p(Y.data_ptr()), Y.stride(0)))
+        return Y
 
     def row_diagnostics(self, X):
         """Per row of Y = X R_op: (PR/d, ||y||_inf^2/||y||_2^2) as two float32 arrays of length T."""

@@ -780,6 +780,25 @@ conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X, uint64_t T, 
   return quant_error_impl(ctx, X, T, stride, bits, 1, clip_ratio, sse, energy);
 }
 
+conqur_status conqur_rotate(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, void* Y, uint64_t y_stride64) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  if (!Y) return fail(ctx, CONQUR_EINVAL, "Y_dev is NULL");
+  const uint64_t esz = ctx->f32 ? 4 : 2;
+  if (y_stride64 < (uint64_t)ctx->d || y_stride64 >= (1ull << 40) || (reinterpret_cast<uintptr_t>(Y) % esz) != 0)
+    return fail(ctx, CONQUR_EINVAL, "Y row stride must be >= d and Y aligned to its element size");
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+  hipStream_t s = ctx->stream;
+  if (ctx->f32)
+    HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
+  GemmArgs g;
+  rotate_args(ctx, X, T, stride, &g);
+  g.C = Y; g.ldc = (int64_t)y_stride64; g.batchC = ctx->dh; g.c_is_f32 = ctx->f32;
+  HIP_TRY(launch_gemm_nt(g, EPI_ACT, ctx->heads, s));
+  return CONQUR_OK;
+}
+
 conqur_status conqur_row_diagnostics(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, float* pr_host,
                                      float* rho_host) {
   conqur_status st = check_x(ctx, X, T64, stride64);
