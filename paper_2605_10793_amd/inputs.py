@@ -155,3 +155,20 @@ def spd_with_spectrum(d: int, sigma: np.ndarray, seed: int) -> Tuple[np.ndarray,
     w = random_orthogonal(d, seed + 101)
     p = (w * np.asarray(sigma, dtype=np.float64)[None, :]) @ w.T
     return 0.5 * (p + p.T), w
+
+
+def hadamard_rotation(d: int, heads: int = 1, seed: int = 0) -> np.ndarray:
+    """Randomised Hadamard initial rotation [heads, dh, dh] (dh a power of two): Sylvester's H / sqrt(dh) with a seeded
+    random sign per row, the fixed-rotation baseline the paper compares against."""
+    dh = d // heads
+    if dh & (dh - 1):
+        raise ValueError("dh must be a power of two")
+    H = np.ones((1, 1), dtype=np.float32)
+    while H.shape[0] < dh:
+        H = np.block([[H, H], [H, -H]])
+    out = np.empty((heads, dh, dh), dtype=np.float32)
+    for h in range(heads):
+        sgn = np.where(_rng(seed, 9000 + h).random(dh) < 0.5, -1.0, 1.0).astype(np.float32)
+        out[h] = (sgn[:, None] * H) / np.float32(np.sqrt(dh))
+    return out
+

@@ -580,3 +580,23 @@ def test_rotate_pins():
     # the corner signs and the quantiser see exactly these rows
     _, S = oc.step_batch(X, True, True)
     assert np.array_equal(S, np.where(Y >= 0, 1, -1))
+
+
+def test_hadamard_initial_rotation_levels_participation():
+    """A randomised Hadamard rotation is orthogonal, has entries +-1/sqrt(d), and spreads outlier-heavy rows to the
+    participation level of random mixing (PR/d from 1/3 up; the paper reports values near 0.3 for Hadamard rotations)."""
+    d = 1024
+    H = I.hadamard_rotation(d, seed=5)
+    assert H.shape == (1, d, d) and np.allclose(np.abs(H), 1.0 / math.sqrt(d))
+    assert np.allclose(H[0].astype(np.float64).T @ H[0], np.eye(d), atol=1e-6)
+    w = I.small_workload(d, 300, seed=33, n_outliers=8)
+    X = I.batch(w, 0)
+    pr_h, _ = O.OracleCalibrator(d, 1, "bf16", H).row_diagnostics(X)
+    pr_0, _ = O.OracleCalibrator(d, 1, "bf16", np.eye(d, dtype=np.float32)).row_diagnostics(X)
+    # a few dominant channels mix like a sum of a few random signs (kurtosis 3 - 2/n): at or above the Gaussian 1/3
+    assert pr_0.mean() < 0.05 and 1.0 / 3.0 < pr_h.mean() < 0.6
+    spike = np.zeros((1, d), dtype=np.float32); spike[0, 77] = 5.0
+    pr_s, rho_s = O.OracleCalibrator(d, 1, "f32", H).row_diagnostics(spike)      # one channel -> equal magnitudes exactly
+    assert np.isclose(pr_s[0], 1.0, rtol=1e-12) and np.isclose(rho_s[0], 1.0 / d, rtol=1e-12)
+    H4 = I.hadamard_rotation(256, heads=4, seed=6)
+    assert H4.shape == (4, 64, 64) and np.allclose(H4[2].astype(np.float64) @ H4[2].T, np.eye(64), atol=1e-6)
