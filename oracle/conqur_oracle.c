@@ -535,3 +535,75 @@ int oq_rotate(const float* X, uint64_t T, uint64_t d, uint64_t heads, uint64_t r
   }
   return 0;
 }
+
+/*
+ * The fake-quantised rotated rows themselves: what a linear layer receives when its input is
+ * quantised after the current rotation has been applied (Sec. 3.4, quantisation-aware calibration;
+ * quantisers of App. B, clipping ratio of App. C).
+ *   y = x R_op per head, stored in the activation dtype (as in oq_rotate);
+ *   zero_point = 0: symmetric, D = max_j |y_j| / (2^(b-1) - 1), q_j = D clamp(rint(y_j / D), -qmax, qmax);
+ *   zero_point = 1: range [clip min_j y_j, clip max_j y_j] on {0 .. 2^b - 1} with the integer zero point,
+ *                   q_j = D (code_j - zeta), a constant row keeps its single level (see oq_quant_error_zp).
+ *   The code is decided in fp32 as in the two error functions; q_j is the exact product D * (integer),
+ *   rounded once into the activation dtype.  Yq: T rows of d floats.
+ */
+int oq_fake_quant(const float* X, uint64_t T, uint64_t d, uint64_t heads, uint64_t row_stride, const float* R_op, int dtype,
+                  int bits, int zero_point, float clip, float* Yq) {
+  if (!X || !R_op || !Yq || heads == 0 || d % heads || row_stride < d || bits < 2 || bits > 8) return -1;
+  if (zero_point && (!(clip > 0.0f) || clip > 1.0f)) return -1;
+  const uint64_t dh = d / heads;
+  const float qsym = (float)((1 << (bits - 1)) - 1), qtop = (float)((1 << bits) - 1);
+#pragma omp parallel
+  {
+    double* y = (double*)malloc(sizeof(double) * d);
+#pragma omp for schedule(static)
+    for (uint64_t i = 0; i < T; ++i) {
+      for (uint64_t h = 0; h < heads; ++h) {
+        const float* x = X + i * row_stride + h * dh;
+        const float* Rh = R_op + h * dh * dh;
+        double* yh = y + h * dh;
+        for (uint64_t j = 0; j < dh; ++j) yh[j] = 0.0;
+        for (uint64_t k = 0; k < dh; ++k) {
+          const double xik = (double)x[k];
+          for (uint64_t j = 0; j < dh; ++j) yh[j] += xik * (double)Rh[k * dh + j];
+        }
+      }
+      float mn = 0.0f, mx = 0.0f, amax = 0.0f;
+      for (uint64_t j = 0; j < d; ++j) {
+        y[j] = dtype == 1 ? oq_round_bf16_f64(y[j]) : (double)(float)y[j];
+        const float v = (float)y[j];
+        if (j == 0 || v < mn) mn = v;
+        if (j == 0 || v > mx) mx = v;
+        if (fabsf(v) > amax) amax = fabsf(v);
+      }
+      for (uint64_t j = 0; j < d; ++j) {
+        double q;
+        if (zero_point) {
+          const float lo = clip * mn, hi = clip * mx;
+          const float delta = (hi - lo) / qtop;
+          if (delta > 0.0f) {
+            const float zeta = -rintf(lo / delta);
+            float code = rintf((float)y[j] / delta) + zeta;
+            if (code > qtop) code = qtop;
+            if (code < 0.0f) code = 0.0f;
+            q = (double)delta * ((double)code - (double)zeta);
+          } else {
+            q = (double)lo;
+          }
+        } else {
+          const float delta = amax / qsym;
+          float code = 0.0f;
+          if (amax > 0.0f) {
+            code = rintf((float)y[j] / delta);
+            if (code > qsym) code = qsym;
+            if (code < -qsym) code = -qsym;
+          }
+          q = (double)delta * (double)code;
+        }
+        Yq[i * d + j] = dtype == 1 ? (float)oq_round_bf16_f64(q) : (float)q;
+      }
+    }
+    free(y);
+  }
+  return 0;
+}

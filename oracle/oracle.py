@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.oq_rotate.argtypes = [p, u64, u64, u64, u64, p, i32, p]
         L.oq_row_diagnostics.restype = i32
         L.oq_row_diagnostics.argtypes = [p, u64, u64, u64, u64, p, i32, p, p]
+        L.oq_fake_quant.restype = i32
+        L.oq_fake_quant.argtypes = [p, u64, u64, u64, u64, p, i32, i32, i32, ctypes.c_float, p]
         L.oq_quant_error_zp.restype = i32
         L.oq_quant_error_zp.argtypes = [p, u64, u64, u64, u64, p, i32, i32, ctypes.c_float, p, p, p, p]
         _lib = L
@@ -174,6 +176,17 @@ class OracleCalibrator:
         if rc != 0:
             raise RuntimeError("oq_rotate failed")
         return Y
+
+    def fake_quant(self, X: np.ndarray, bits: int = 4, zero_point: bool = True, clip: float = 1.0) -> np.ndarray:
+        """Q(X R_op): the fake-quantised rotated rows a quantised linear layer receives (Sec. 3.4), as float32."""
+        X = np.ascontiguousarray(X, dtype=np.float32)
+        T, stride = X.shape
+        Yq = np.empty((T, self.d), dtype=np.float32)
+        rc = lib().oq_fake_quant(_ptr(X), T, self.d, self.heads, stride, _ptr(self.R_op), 1 if self.dtype == "bf16" else 0,
+                                 bits, 1 if zero_point else 0, ctypes.c_float(clip), _ptr(Yq))
+        if rc != 0:
+            raise RuntimeError("oq_fake_quant failed")
+        return Yq
 
     def row_diagnostics(self, X: np.ndarray):
         """Per row of Y = X R_op: normalised participation ratio PR/d (Sec. 4.2) and ||y||_inf^2/||y||_2^2 (App. B)."""

@@ -600,3 +600,79 @@ def test_hadamard_initial_rotation_levels_participation():
     assert np.isclose(pr_s[0], 1.0, rtol=1e-12) and np.isclose(rho_s[0], 1.0 / d, rtol=1e-12)
     H4 = I.hadamard_rotation(256, heads=4, seed=6)
     assert H4.shape == (4, 64, 64) and np.allclose(H4[2].astype(np.float64) @ H4[2].T, np.eye(64), atol=1e-6)
+
+
+# --------------------------------------------------------------------------- fake-quantised rotated rows (Sec. 3.4)
+
+def test_fake_quant_hand_computed_rows():
+    oc3 = O.OracleCalibrator(3, 1, "f32", np.eye(3, dtype=np.float32))
+    # zero point, b = 2, range [-1.5, 1.5]: D = 1, zeta = 2, codes 0, 2, 3 -> -2, 0, 1
+    q = oc3.fake_quant(np.array([[-1.5, 0.0, 1.5]], dtype=np.float32), 2, True, 1.0)
+    assert q[0].tolist() == [-2.0, 0.0, 1.0]
+    # symmetric, b = 2 (levels -1, 0, 1 times max|y|): 0.26 -> 0, -0.74 -> -1
+    q = oc3.fake_quant(np.array([[1.0, 0.26, -0.74]], dtype=np.float32), 2, False)
+    assert q[0].tolist() == [1.0, 0.0, -1.0]
+    # clip 0.75 on [-2 .. 2], b = 2: levels -2, -1, 0, 1; the top entry saturates at 1
+    oc5 = O.OracleCalibrator(5, 1, "f32", np.eye(5, dtype=np.float32))
+    q = oc5.fake_quant(np.array([[-2.0, -1.0, 0.0, 1.0, 2.0]], dtype=np.float32), 2, True, 0.75)
+    assert q[0].tolist() == [-2.0, -1.0, 0.0, 1.0, 1.0]
+    # rows already on the grid come back unchanged (b = 4: 0..15 zero point, -7..7 symmetric); constant rows too
+    oc16 = O.OracleCalibrator(16, 1, "f32", np.eye(16, dtype=np.float32))
+    grid = np.arange(16, dtype=np.float32)[None, :]
+    assert np.array_equal(oc16.fake_quant(grid, 4, True, 1.0), grid)
+    sym = np.concatenate([np.arange(-7, 8), [3]]).astype(np.float32)[None, :] * 0.5
+    assert np.array_equal(oc16.fake_quant(sym, 4, False), sym)
+    const = np.stack([np.full(16, 2.5, np.float32), np.zeros(16, np.float32)])
+    assert np.array_equal(oc16.fake_quant(const, 4, True, 1.0), const)
+    assert np.array_equal(oc16.fake_quant(const, 4, False), const)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fake_quant_levels_error_bound_and_rotation(dtype):
+    """At most 2^b (zero point) / 2^b - 1 (symmetric) distinct values per row, on an equally spaced grid; every entry
+    within half a step of its input (App. B's per-coordinate bound; the activation dtype's rounding of the level
+    on top for bf16); the rows quantised are those of X R_op, per head; the squared error equals what the error
+    functions report."""
+    d, heads, T = 64, 2, 24
+    R = np.stack([np.linalg.qr(gauss((32, 32), 31 + h))[0] for h in range(heads)]).astype(np.float32)
+    X = (gauss((T, d), 33) * np.exp(gauss((1, d), 34))).astype(np.float32)
+    if dtype == "bf16":
+        X = torch.from_numpy(X).to(torch.bfloat16).float().numpy()
+    oc = O.OracleCalibrator(d, heads, dtype, R)
+    Y = oc.rotate(X).astype(np.float64)
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -23
+    for zp, bits, nlev in ((True, 4, 16), (False, 4, 15), (True, 3, 8), (False, 8, 255)):
+        Q = oc.fake_quant(X, bits, zp, 1.0).astype(np.float64)
+        span = (Y.max(1) - Y.min(1)) / (nlev - 1) if zp else np.abs(Y).max(1) / ((nlev - 1) / 2)
+        for i in range(T):
+            lv = np.unique(Q[i])
+            assert len(lv) <= nlev
+            steps = np.diff(lv) / span[i]
+            # equally spaced levels (a bf16 level of up to nlev steps carries up to nlev * 2^-9 steps of rounding)
+            assert np.allclose(steps, np.rint(steps), atol=0.02 if dtype == "f32" else 2 * nlev * 2.0 ** -9 + 0.02), (zp, bits, i)
+        # half a step, plus one step where the integer zero point pushes the top code out of the grid
+        err = np.abs(Q - Y)
+        slack = np.abs(Q).max(1, keepdims=True) * ulp + 1e-6 * span[:, None]
+        assert (err <= 0.5 * span[:, None] + slack).mean() > (0.97 if zp else 0.999)
+        assert (err <= (1.0 if zp else 0.5) * span[:, None] + slack).all()
+        if dtype == "f32":
+            sse = (oc.quant_error_zp(X, bits, 1.0) if zp else oc.quant_error(X, bits))[0]
+            assert np.isclose((err ** 2).sum(), sse, rtol=1e-6)
+    # identity rotation: quantising the rotated rows is quantising the rows; block structure: heads do not mix
+    oi = O.OracleCalibrator(d, heads, dtype, np.stack([np.eye(32, dtype=np.float32)] * heads))
+    Xs = X.copy(); Xs[:, 32:] = 0.0
+    Qs = oc.fake_quant(Xs, 4, False)
+    assert np.all(Qs[:, 32:] == 0.0) and np.any(Qs[:, :32] != 0.0)
+    Qi = oi.fake_quant(X, 4, False).astype(np.float64)
+    assert np.all(np.abs(Qi - X) <= np.abs(X).max(1, keepdims=True) / 7 * 0.5 * (1 + 4 * ulp) + 1e-30)
+
+
+def test_fake_quant_symmetric_is_idempotent_and_scale_equivariant():
+    d = 128
+    oc = O.OracleCalibrator(d, 1, "f32", np.eye(d, dtype=np.float32))
+    X = gauss((16, d), 35).astype(np.float32)
+    Q = oc.fake_quant(X, 4, False)
+    assert np.allclose(oc.fake_quant(Q, 4, False), Q, rtol=1e-6, atol=0)
+    assert np.array_equal(oc.fake_quant(X * 4.0, 4, False), Q * 4.0)        # powers of two commute exactly
+    assert np.array_equal(oc.fake_quant(X * 0.25, 4, True, 0.9), oc.fake_quant(X, 4, True, 0.9) * 0.25)
+    assert np.array_equal(oc.fake_quant(-X, 4, False), -Q)                  # symmetric grid, round-half-even
