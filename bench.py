@@ -147,6 +147,14 @@ def main():
         zp_ms += cal.timing()["quant_error"]
         zp_rel = s_zp / e_zp
     zp_ms /= K
+    # the same quantiser emitting the fake-quantised rotated rows (the input of a quantised layer): reads Y, writes Yq
+    import torch
+    Yq = torch.empty((T, d), dtype=dev[0].dtype, device=dev[0].device)
+    emit_ms = 0.0
+    for i in range(K):
+        cal.rotate_quant(dev[i % n_distinct], 4, True, 0.9, Yq)
+        emit_ms += cal.timing()["quant_error"]
+    emit_ms /= K
     step_ms = whole["step"]
     gemm_ms = acc["rotate"] + acc["accumulate"]
     dh = w.dh
@@ -197,6 +205,10 @@ def main():
     out["roofline_quant_error_zp"] = {
         "bound": "hbm", "achieved": y_bytes / (zp_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": y_bytes / (zp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "ms": zp_ms, "clip_ratio": 0.9, "int4_rel_err": zp_rel,
+    }
+    out["roofline_rotate_quant_emit"] = {
+        "bound": "hbm", "achieved": 2 * y_bytes / (emit_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": 2 * y_bytes / (emit_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "ms": emit_ms, "clip_ratio": 0.9,
     }
     if w.dh == 128 and w.dtype == "bf16":
         # heads of width 128 take the fused step kernel: bound by reading X once (256 bytes per token and head)

@@ -164,6 +164,23 @@ conqur_status conqur_rotate(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint
                             uint64_t y_row_stride_elems);
 
 /*
+ * The fake-quantised rotated rows: Yq = Q(X R_op), what a linear layer receives when its
+ * input is quantised after the current rotation has been applied (quantisation-aware
+ * calibration, Sec. 3.4).  Y = X R_op as in conqur_rotate; each row of width d is then
+ * quantised per token with the symmetric quantiser of conqur_quant_error (zero_point =
+ * 0; clip_ratio ignored) or the zero-point quantiser of conqur_quant_error_zp
+ * (zero_point = 1, clip_ratio in (0, 1]) and written as the level values q (not the
+ * integer codes), rounded once into act_dtype.  Yq_dev: DEVICE, T rows of
+ * yq_row_stride_elems >= d elements of act_dtype, base and row pitch multiples of 16
+ * bytes, owned by the caller, must not overlap X.  Asynchronous on the context's stream;
+ * does not change the calibration state.  Errors: CONQUR_EINVAL (bits outside [2, 8],
+ * zero_point > 1, clip_ratio outside (0, 1], NULL / misaligned Yq_dev, bad X
+ * arguments), CONQUR_EHIP.
+ */
+conqur_status conqur_rotate_quant(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems, uint32_t bits,
+                                  uint32_t zero_point, float clip_ratio, void* Yq_dev, uint64_t yq_row_stride_elems);
+
+/*
  * Per-row diagnostics of the rotated activations: Y = X R_op per head, stored in
  * act_dtype, then per token over the whole row of width d
  *   pr  = ||y||_2^4 / (d ||y||_4^4)   normalised participation ratio (Sec. 4.2), in [1/d, 1]

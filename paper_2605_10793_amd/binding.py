@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
-    "conqur_quant_error", "conqur_quant_error_zp", "conqur_rotate", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
+    "conqur_quant_error", "conqur_quant_error_zp", "conqur_rotate", "conqur_rotate_quant", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
     "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
                                             ctypes.POINTER(ctypes.c_double)]
         L.conqur_rotate.restype = i32
         L.conqur_rotate.argtypes = [vp, vp, u64, u64, vp, u64]
+        L.conqur_rotate_quant.restype = i32
+        L.conqur_rotate_quant.argtypes = [vp, vp, u64, u64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_float, vp, u64]
         L.conqur_row_diagnostics.restype = i32
         L.conqur_row_diagnostics.argtypes = [vp, vp, u64, u64, vp, vp]
         L.conqur_get_state.restype = i32
@@ -194,6 +196,18 @@ class Calibrator:
             raise ValueError("Y must be a [T, >= d] tensor of X's dtype with unit column stride")
         self._check(self._lib.conqur_rotate(self._h, p, T, stride, ctypes.c_void_p(Y.data_ptr()), Y.stride(0)))
         return Y
+
+    def rotate_quant(self, X, bits: int = 4, zero_point: bool = True, clip_ratio: float = 1.0, Yq=None):
+        """Yq = Q(X R_op): per-token fake-quantised rotated rows in X's dtype (allocated here unless given); asynchronous."""
+        import torch
+        p, T, stride = self._x(X)
+        if Yq is None:
+            Yq = torch.empty((T, self.d), dtype=X.dtype, device=X.device)
+        if Yq.dtype != X.dtype or Yq.dim() != 2 or Yq.shape[0] != T or Yq.shape[1] < self.d or Yq.stride(1) != 1:
+            raise ValueError("Yq must be a [T, >= d] tensor of X's dtype with unit column stride")
+        self._check(self._lib.conqur_rotate_quant(self._h, p, T, stride, bits, 1 if zero_point else 0, ctypes.c_float(clip_ratio),
+                                                  ctypes.c_void_p(Yq.data_ptr()), Yq.stride(0)))
+        return Yq
 
     def row_diagnostics(self, X):
         """Per row of Y = X R_op: (PR/d, ||y||_inf^2/||y||_2^2) as two float32 arrays of length T."""

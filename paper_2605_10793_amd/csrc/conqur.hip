@@ -751,7 +751,7 @@ static conqur_status quant_error_impl(conqur_ctx* ctx, const void* X, uint64_t T
     StageTimer tm(ctx, ST_QERR);
     // a batch's per-row results are small: the host adds them (fixed order) instead of one more kernel launch
     HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, zero_point, clip, ctx->row_sse, ctx->row_en,
-                               T <= kHostSumRows ? nullptr : ctx->qsum, s));
+                               T <= kHostSumRows ? nullptr : ctx->qsum, nullptr, 0, s));
   }
   }
   double host[2] = {0.0, 0.0};
@@ -796,6 +796,39 @@ conqur_status conqur_rotate(conqur_ctx* ctx, const void* X, uint64_t T64, uint64
   rotate_args(ctx, X, T, stride, &g);
   g.C = Y; g.ldc = (int64_t)y_stride64; g.batchC = ctx->dh; g.c_is_f32 = ctx->f32;
   HIP_TRY(launch_gemm_nt(g, EPI_ACT, ctx->heads, s));
+  return CONQUR_OK;
+}
+
+conqur_status conqur_rotate_quant(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, uint32_t bits,
+                                  uint32_t zero_point, float clip_ratio, void* Yq, uint64_t yq_stride64) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  if (bits < 2 || bits > 8) return fail(ctx, CONQUR_EINVAL, "bits must be in [2, 8]");
+  if (zero_point > 1) return fail(ctx, CONQUR_EINVAL, "zero_point must be 0 or 1");
+  if (zero_point && (!(clip_ratio > 0.0f) || clip_ratio > 1.0f)) return fail(ctx, CONQUR_EINVAL, "clip_ratio must be in (0, 1]");
+  if (!Yq) return fail(ctx, CONQUR_EINVAL, "Yq_dev is NULL");
+  // the quantising kernel stores 16-byte chunks
+  if (yq_stride64 < (uint64_t)ctx->d || yq_stride64 >= (1ull << 40) || (reinterpret_cast<uintptr_t>(Yq) % 16) != 0 ||
+      (yq_stride64 * (ctx->f32 ? 4 : 2)) % 16 != 0)
+    return fail(ctx, CONQUR_EINVAL, "Yq row stride must be >= d and Yq and its rows aligned to 16 bytes");
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+  hipStream_t s = ctx->stream;
+  StageTimer whole(ctx, ST_QUANT, 1);   // the stages are timed in the slots of conqur_quant_error
+  {
+    StageTimer tm(ctx, ST_QROT);
+    if (ctx->f32)
+      HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
+    GemmArgs g;
+    rotate_args(ctx, X, T, stride, &g);
+    g.C = ctx->Y; g.ldc = ctx->d; g.batchC = ctx->dh; g.c_is_f32 = ctx->f32;
+    HIP_TRY(launch_gemm_nt(g, EPI_ACT, ctx->heads, s));
+  }
+  {
+    StageTimer tm(ctx, ST_QERR);
+    HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, (int)zero_point, clip_ratio, ctx->row_sse,
+                               ctx->row_en, nullptr, Yq, (int64_t)yq_stride64, s));
+  }
   return CONQUR_OK;
 }
 

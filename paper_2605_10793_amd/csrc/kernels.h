@@ -81,8 +81,9 @@ hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int 
 
 // Per-row fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse / row_en, then their sums over rows:
 // out[0] = SSE, out[1] = energy (skipped if out is null).  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
+// Q non-null: the quantised rows are also written to Q [T][ldq] in Y's element type (Q must not overlap Y).
 hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
-                              float* row_sse, float* row_en, double* out, hipStream_t s);
+                              float* row_sse, float* row_en, double* out, void* Q, int64_t ldq, hipStream_t s);
 
 // Per-row diagnostics of Y [T][ld] (bf16 or fp32): row_pr = ||y||_2^4 / (d ||y||_4^4), row_rho = ||y||_inf^2 / ||y||_2^2
 // (0, 0 for a row with zero or non-finite energy).

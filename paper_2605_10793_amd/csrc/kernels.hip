@@ -361,9 +361,12 @@ __global__ void __launch_bounds__(256) k_axpy(float* __restrict__ X, const float
 // results go to row_sse / row_en.
 // ZP: the zero-point quantiser of App. B instead of the symmetric one: range [clip*min, clip*max] on the unsigned grid
 // {0 .. qmax}, D = range / qmax, integer zero point zeta = -rint(lo / D), code = clamp(rint(y / D) + zeta, 0, qmax).
-template <bool F32, bool ZP>
+// EMIT: the quantised rows q are also written out in the activation dtype (Q, row stride ldq): what a linear layer with
+// quantised input receives during quantisation-aware calibration (Sec. 3.4).
+template <bool F32, bool ZP, bool EMIT>
 __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y, int64_t T, int64_t ld, int d, float qmax,
-                                                     float clip, float* __restrict__ row_sse, float* __restrict__ row_en) {
+                                                     float clip, float* __restrict__ row_sse, float* __restrict__ row_en,
+                                                     void* __restrict__ Q, int64_t ldq) {
   constexpr int EPC = F32 ? 4 : 8;  // elements per 16-byte chunk
   constexpr int NC = 4;             // chunks cached per thread
   __shared__ float shm[4], shn[4], shs[4], she[4];
@@ -432,8 +435,9 @@ __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y,
     inv_delta = amax > 0.0f ? 1.0f / delta : 0.0f;
   }
   float sse = 0.0f, en = 0.0f;
-  auto score = [&](const uint4& v) {
-    float f[EPC];
+  uint4* const qrow = EMIT ? reinterpret_cast<uint4*>(reinterpret_cast<char*>(Q) + row * ldq * (F32 ? 4 : 2)) : nullptr;
+  auto score = [&](const uint4& v, int c) {
+    float f[EPC], qv[EPC];
     expand(v, f);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) {
@@ -442,18 +446,30 @@ __global__ void __launch_bounds__(256) k_quant_error(const void* __restrict__ Y,
         const float code = fminf(fmaxf(rintf(f[e] * inv_delta) + zeta, 0.0f), qmax);
         // a constant row (delta = 0) has the single level lo
         err = delta > 0.0f ? fmaf(-delta, code - zeta, f[e]) : f[e] - lo;
+        qv[e] = delta > 0.0f ? delta * (code - zeta) : lo;
       } else {
         const float code = fminf(fmaxf(rintf(f[e] * inv_delta), -qmax), qmax);
         err = fmaf(-delta, code, f[e]);
+        qv[e] = delta * code;
       }
       sse = fmaf(err, err, sse);
       en = fmaf(f[e], f[e], en);
     }
+    if constexpr (EMIT) {
+      uint4 o;
+      if constexpr (F32) {
+        o = make_uint4(__float_as_uint(qv[0]), __float_as_uint(qv[1]), __float_as_uint(qv[2]), __float_as_uint(qv[3]));
+      } else {
+        o = make_uint4(f32x2_to_bf16x2(qv[0], qv[1]), f32x2_to_bf16x2(qv[2], qv[3]), f32x2_to_bf16x2(qv[4], qv[5]),
+                       f32x2_to_bf16x2(qv[6], qv[7]));
+      }
+      qrow[c] = o;
+    }
   };
 #pragma unroll
   for (int q = 0; q < NC; ++q)
-    if ((int)threadIdx.x + 256 * q < nch) score(cache[q]);
-  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) score(y[c]);
+    if ((int)threadIdx.x + 256 * q < nch) score(cache[q], (int)threadIdx.x + 256 * q);
+  for (int c = threadIdx.x + 256 * NC; c < nch; c += 256) score(y[c], c);
   sse = wave_sum(sse);
   en = wave_sum(en);
   if (lane == 0) { shs[wave] = sse; she[wave] = en; }
@@ -673,18 +689,27 @@ hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
-                              float* row_sse, float* row_en, double* out, hipStream_t s) {
-  const float qmax = zero_point ? (float)((1 << bits) - 1) : (float)((1 << (bits - 1)) - 1);
+namespace {
+template <bool EMIT>
+void launch_quant_kernel(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, float qmax, int zero_point, float clip,
+                         float* row_sse, float* row_en, void* Q, int64_t ldq, hipStream_t s) {
   const dim3 grid((unsigned)T);
   if (y_is_f32 && zero_point)
-    hipLaunchKernelGGL((k_quant_error<true, true>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
+    hipLaunchKernelGGL((k_quant_error<true, true, EMIT>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en, Q, ldq);
   else if (y_is_f32)
-    hipLaunchKernelGGL((k_quant_error<true, false>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
+    hipLaunchKernelGGL((k_quant_error<true, false, EMIT>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en, Q, ldq);
   else if (zero_point)
-    hipLaunchKernelGGL((k_quant_error<false, true>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
+    hipLaunchKernelGGL((k_quant_error<false, true, EMIT>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en, Q, ldq);
   else
-    hipLaunchKernelGGL((k_quant_error<false, false>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en);
+    hipLaunchKernelGGL((k_quant_error<false, false, EMIT>), grid, dim3(256), 0, s, Y, T, ld, d, qmax, clip, row_sse, row_en, Q, ldq);
+}
+}  // namespace
+
+hipError_t launch_quant_error(const void* Y, int y_is_f32, int64_t T, int64_t ld, int d, int bits, int zero_point, float clip,
+                              float* row_sse, float* row_en, double* out, void* Q, int64_t ldq, hipStream_t s) {
+  const float qmax = zero_point ? (float)((1 << bits) - 1) : (float)((1 << (bits - 1)) - 1);
+  if (Q) launch_quant_kernel<true>(Y, y_is_f32, T, ld, d, qmax, zero_point, clip, row_sse, row_en, Q, ldq, s);
+  else launch_quant_kernel<false>(Y, y_is_f32, T, ld, d, qmax, zero_point, clip, row_sse, row_en, nullptr, 0, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !out) return e;   // out == null: the caller sums the per-row results itself
   hipLaunchKernelGGL(k_sum_rows, dim3(1), dim3(1024), 0, s, row_sse, row_en, T, out);

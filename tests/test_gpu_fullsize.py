@@ -91,6 +91,17 @@ def test_full_batch_elementwise(B, name):
         sg, eg = cal.quant_error_zp(Xd, 4, 0.9)
         say(f"  {name}: zero-point int4 (clip 0.9) SSE gpu={sg:.6e} oracle={so:.6e}")
         assert abs(sg - so) <= 1e-3 * so and abs(eg - eo) <= 1e-3 * eo
+        # the emitted fake-quantised rows, whole batch, against the oracle's
+        Qg = cal.rotate_quant(Xd, 4, True, 0.9).float().cpu().numpy()
+        Qo = oc.fake_quant(X, 4, True, 0.9)
+        Yo = oc.rotate(X)
+        stepw = (0.9 * (Yo.max(1) - Yo.min(1)) / 15)[:, None]
+        diff = np.abs(Qg - Qo)
+        ulp = 2.0 ** -8 if w.dtype == "bf16" else 1e-6
+        assert np.all(diff <= stepw * (1 + 2.0 ** -6) + 2 * ulp * np.abs(Qo))
+        near = diff <= 4 * ulp * (np.abs(Qo) + stepw)
+        say(f"  {name}: fake-quant rows: {100 * (1 - near.mean()):.4f} % of the entries on a neighbouring level")
+        assert near.mean() >= 0.997
         # Procrustes from the oracle's M, checked by the polar factor's defining properties
         M = oc.M[0]
         cal.set_state(M=M.astype(np.float32))

@@ -141,6 +141,30 @@ def compare_quant(B, cal, oc, X, w, tag):
         say(f"  {tag}: zero-point int4 clip {clip}: rel.err gpu={sg / eg:.6e} oracle={so / eo:.6e}")
         assert abs(sg - so) <= TOL_REL * so + 1e-30
         assert abs(eg - eo) <= TOL_REL * eo
+    # the fake-quantised rotated rows themselves (what a quantised layer receives); output stride exercised again
+    rows_ok = np.isfinite(Yo).all(axis=1)
+    ulp = 2.0 ** -8 if w.dtype == "bf16" else 1e-6    # fp32: the accuracy of the split-precision products, as for Y above
+    for zp, clip in ((True, 0.9), (True, 1.0), (False, 1.0)):
+        Qbuf = torch.zeros((X.shape[0], w.d + 8), dtype=Xd.dtype, device=Xd.device)
+        cal.rotate_quant(Xd, 4, zp, clip, Qbuf)
+        torch.cuda.synchronize()
+        Qg = Qbuf[:, :w.d].float().cpu().numpy().astype(np.float64)[rows_ok]
+        Qo = oc.fake_quant(X, 4, zp, clip).astype(np.float64)[rows_ok]
+        Yr = Yo.astype(np.float64)[rows_ok]
+        step = clip * (Yr.max(1) - Yr.min(1)) / 15 if zp else np.abs(Yr).max(1) / 7
+        diff = np.abs(Qg - Qo)
+        # a value of Y that differs by an ulp between the two sides can land on the neighbouring level, never further;
+        # a row whose extreme value differs by an ulp has its whole grid moved by that relative amount
+        near = diff <= 4 * ulp * (np.abs(Qo) + step[:, None]) + 1e-30
+        assert np.all(diff <= step[:, None] * (1 + 2.0 ** -6) + 2 * ulp * np.abs(Qo) + 1e-30), tag   # + the levels' own rounding
+        say(f"  {tag}: fake-quant zp={zp} clip={clip}: {100 * (1 - near.mean()):.4f} % of the entries on a neighbouring level")
+        assert near.mean() >= (0.997 if w.dtype == "bf16" else 0.9995), tag
+        assert len(np.unique(Qg[0])) <= (16 if zp else 15)
+        assert not Qbuf[:, w.d:].any()
+        # the squared error of the emitted rows is the one the error entry points report
+        sg = (cal.quant_error_zp(Xd, 4, clip) if zp else cal.quant_error(Xd, 4))[0]
+        sse_rows = ((Qbuf[:, :w.d].double() - Ybuf[:, :w.d].double()) ** 2).sum(1).cpu().numpy()[rows_ok].sum()
+        assert abs(sse_rows - sg) <= (2e-2 if w.dtype == "bf16" else 1e-4) * sg + 1e-30, (tag, sse_rows, sg)
 
 
 def run_stream(B, w, n_batches, check_R, tokens=None, **cal_kwargs):
