@@ -3,7 +3,30 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace conqur {
+
+// A kernel's dynamic-LDS limit (hipFuncSetAttribute) belongs to the device that is current when it is set: launchers
+// raise it once per device and kernel.  One bit per device ordinal; ordinals beyond 63 set it on every launch.
+class PerDeviceOnce {
+ public:
+  template <typename F>
+  hipError_t run(F&& set) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0ull;
+    if (bit && (done_.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = set();
+    if (e == hipSuccess && bit) done_.fetch_or(bit, std::memory_order_release);
+    return e;
+  }
+
+ private:
+  std::atomic<uint64_t> done_{0};
+};
+
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));

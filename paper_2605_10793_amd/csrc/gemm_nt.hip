@@ -397,6 +397,43 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
       }
     rsum = wave_sum_d(rsum);
     if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+  } else if constexpr (EPI == EPI_XLAST) {
+    const int64_t boff = (int64_t)bz * g.batchC;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = nw + j * 32 + col;
+        if (n >= g.N) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int mb = mw + i * 32 + 8 * q + 4 * half;   // 4 consecutive rows mb .. mb+3 (M is a multiple of 4)
+          if (mb >= g.M) continue;
+          const float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
+          uint2 hi, lo;
+          hi.x = f32x2_to_bf16x2(v0, v1);
+          hi.y = f32x2_to_bf16x2(v2, v3);
+          const float h0 = __uint_as_float(hi.x << 16), h1 = __uint_as_float(hi.x & 0xffff0000u);
+          const float h2 = __uint_as_float(hi.y << 16), h3 = __uint_as_float(hi.y & 0xffff0000u);
+          lo.x = f32x2_to_bf16x2(v0 - h0, v1 - h1);
+          lo.y = f32x2_to_bf16x2(v2 - h2, v3 - h3);
+          const int64_t off = boff + (int64_t)mb * g.ldc + n;
+          // hi + lo has at most 17 significant bits: the fp32 sum is exact
+          g.C32[off] = h0 + __uint_as_float(lo.x << 16);
+          g.C32[off + g.ldc] = h1 + __uint_as_float(lo.x & 0xffff0000u);
+          g.C32[off + 2 * g.ldc] = h2 + __uint_as_float(lo.y << 16);
+          g.C32[off + 3 * g.ldc] = h3 + __uint_as_float(lo.y & 0xffff0000u);
+          bf16_bits* pn = g.Pn + off;
+          pn[0] = (bf16_bits)hi.x; pn[g.ldc] = (bf16_bits)(hi.x >> 16);
+          pn[2 * g.ldc] = (bf16_bits)hi.y; pn[3 * g.ldc] = (bf16_bits)(hi.y >> 16);
+          pn += g.plane_out;
+          pn[0] = (bf16_bits)lo.x; pn[g.ldc] = (bf16_bits)(lo.x >> 16);
+          pn[2 * g.ldc] = (bf16_bits)lo.y; pn[3 * g.ldc] = (bf16_bits)(lo.y >> 16);
+          bf16_bits* pt = g.Pt + boff + (int64_t)n * g.ldc + mb;
+          *reinterpret_cast<uint2*>(pt) = hi;
+          *reinterpret_cast<uint2*>(pt + g.plane_out) = lo;
+        }
+      }
   } else {  // EPI_XOUT
     const int64_t boff = (int64_t)bz * g.batchC;
 #pragma unroll
@@ -467,13 +504,12 @@ template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16>
 hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
   static_assert(smem <= 160 * 1024, "LDS of one CU");
-  static bool configured = false;
+  static PerDeviceOnce configured;
   auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, NSTAGE, EPI, F16>;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  hipError_t e = configured.run([&] {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  });
+  if (e != hipSuccess) return e;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, 1, batch);
   hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), smem, stream, a, tiles_m, tiles_n);
@@ -509,11 +545,13 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
       batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
     return hipErrorInvalidValue;
+  if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3))) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
     case EPI_ACT: return launch_epi<EPI_ACT>(a, batch, stream);
     case EPI_F32: return a.ab_f16 ? launch_epi<EPI_F32, true>(a, batch, stream) : launch_epi<EPI_F32>(a, batch, stream);
     case EPI_GRAMW: return launch_epi<EPI_GRAMW>(a, batch, stream);
+    case EPI_XLAST: return launch_epi<EPI_XLAST>(a, batch, stream);
     case EPI_XOUT: return launch_epi<EPI_XOUT>(a, batch, stream);
     case EPI_SQUARE: return launch_epi<EPI_SQUARE>(a, batch, stream);
     case EPI_FRO2: return launch_epi<EPI_FRO2>(a, batch, stream);

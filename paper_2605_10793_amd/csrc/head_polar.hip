@@ -12,8 +12,8 @@
 // (an accumulator lane owns 4 consecutive rows of one column, i.e. 8 contiguous bytes of the
 // transposed matrix: computing the product in both orientations replaces the scattered
 // 2-byte stores a single orientation would need for its own layout).
-// The last step writes what the closing iterations read: the fp32 iterate, three
-// transposed and two natural bf16 split planes.
+// The last step writes what the closing iterations read: the iterate rounded to two bf16
+// split planes, as fp32 and as two planes of each layout.
 #include "kernels.h"
 
 namespace conqur {
@@ -109,7 +109,10 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
     __syncthreads();
   }
 
-  // Hand-over to the closing iterations: fp32 X, 3 transposed planes (from X') and 2 natural planes (from X'^T).
+  // Hand-over to the closing iterations: the iterate rounded to two bf16 planes (16 significant bits), that value as
+  // fp32 X, as 2 transposed planes (from X') and as 2 natural planes (from X'^T): the closing Gram matrix is then exact
+  // with 4 plane products (fp32 X and the transposed planes come from the same accumulators; the natural planes, from
+  // the other orientation of the product, feed only the small correction product of the closing step).
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -123,26 +126,27 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
         for (int ii = 0; ii < 4; ++ii) {
           v[ii] = acc[i][j][4 * jj + ii];
           t[ii] = accT[i][j][4 * jj + ii];
-          X32[hoff + (int64_t)(m0 + ii) * DH + n] = v[ii];
         }
+        uint2 hi, lo;
+        hi.x = f32x2_to_bf16x2(v[0], v[1]);
+        hi.y = f32x2_to_bf16x2(v[2], v[3]);
+        const float h[4] = {__uint_as_float(hi.x << 16), __uint_as_float(hi.x & 0xffff0000u), __uint_as_float(hi.y << 16),
+                            __uint_as_float(hi.y & 0xffff0000u)};
+        lo.x = f32x2_to_bf16x2(v[0] - h[0], v[1] - h[1]);
+        lo.y = f32x2_to_bf16x2(v[2] - h[2], v[3] - h[3]);
+        const float l[4] = {__uint_as_float(lo.x << 16), __uint_as_float(lo.x & 0xffff0000u), __uint_as_float(lo.y << 16),
+                            __uint_as_float(lo.y & 0xffff0000u)};
 #pragma unroll
-        for (int p = 0; p < 3; ++p) {
-          uint2 pk;
-          pk.x = f32x2_to_bf16x2(v[0], v[1]);
-          pk.y = f32x2_to_bf16x2(v[2], v[3]);
-          v[0] -= __uint_as_float(pk.x << 16); v[1] -= __uint_as_float(pk.x & 0xffff0000u);
-          v[2] -= __uint_as_float(pk.y << 16); v[3] -= __uint_as_float(pk.y & 0xffff0000u);
-          *reinterpret_cast<uint2*>(Pt + p * plane + hoff + (int64_t)n * DH + m0) = pk;   // X^T[c = n][r = m0 ..]
-        }
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-          uint2 pk;
-          pk.x = f32x2_to_bf16x2(t[0], t[1]);
-          pk.y = f32x2_to_bf16x2(t[2], t[3]);
-          t[0] -= __uint_as_float(pk.x << 16); t[1] -= __uint_as_float(pk.x & 0xffff0000u);
-          t[2] -= __uint_as_float(pk.y << 16); t[3] -= __uint_as_float(pk.y & 0xffff0000u);
-          *reinterpret_cast<uint2*>(Pn + p * plane + hoff + (int64_t)n * DH + m0) = pk;   // accT: X[r = n][c = m0 ..]
-        }
+        for (int ii = 0; ii < 4; ++ii) X32[hoff + (int64_t)(m0 + ii) * DH + n] = h[ii] + l[ii];   // exact: <= 17 bits
+        *reinterpret_cast<uint2*>(Pt + hoff + (int64_t)n * DH + m0) = hi;            // X^T[c = n][r = m0 ..]
+        *reinterpret_cast<uint2*>(Pt + plane + hoff + (int64_t)n * DH + m0) = lo;
+        uint2 thi, tlo;
+        thi.x = f32x2_to_bf16x2(t[0], t[1]);
+        thi.y = f32x2_to_bf16x2(t[2], t[3]);
+        tlo.x = f32x2_to_bf16x2(t[0] - __uint_as_float(thi.x << 16), t[1] - __uint_as_float(thi.x & 0xffff0000u));
+        tlo.y = f32x2_to_bf16x2(t[2] - __uint_as_float(thi.y << 16), t[3] - __uint_as_float(thi.y & 0xffff0000u));
+        *reinterpret_cast<uint2*>(Pn + hoff + (int64_t)n * DH + m0) = thi;           // accT: X[r = n][c = m0 ..]
+        *reinterpret_cast<uint2*>(Pn + plane + hoff + (int64_t)n * DH + m0) = tlo;
       }
     }
 }
@@ -152,13 +156,12 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
                                 bf16_bits* Pn, bf16_bits* Pt, int64_t plane, hipStream_t s) {
   if (heads < 1 || sched.nsteps < 1 || sched.nsteps > kPolarScheduleMax) return hipErrorInvalidValue;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_polar128), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kSmemBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static PerDeviceOnce configured;
+  hipError_t e = configured.run([] {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_polar128), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kSmemBytes);
+  });
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_head_polar128, dim3(heads), dim3(256), kSmemBytes, s, Xn0, Xt0, sched, X32, Pn, Pt, plane);
   return hipGetLastError();
 }

@@ -273,16 +273,16 @@ hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, in
   const int64_t tiles = (T + TT - 1) / TT;
   const int64_t tokens_per_split = (tiles + nsplit - 1) / nsplit * TT;
   const dim3 grid(heads, nsplit);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_step128<true>),
+  static PerDeviceOnce configured;
+  hipError_t e = configured.run([] {
+    hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_step128<true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_step128<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (r == hipSuccess)
+      r = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_step128<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
                               kSmemBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+    return r;
+  });
+  if (e != hipSuccess) return e;
   if (St)
     hipLaunchKernelGGL(k_head_step128<true>, grid, dim3(512), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
                        L, rows, skipped, nonfinite, St, pitch);
