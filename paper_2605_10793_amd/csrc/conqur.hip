@@ -25,6 +25,7 @@ constexpr SegList kSeg1 = {1, {0}, {0}};
 constexpr SegList kSeg3 = {3, {1, 0, 0}, {0, 1, 0}};                     // two planes each: hi*hi + hi*lo + lo*hi
 constexpr SegList kSeg6 = {6, {2, 1, 0, 1, 0, 0}, {0, 1, 2, 0, 1, 0}};  // all terms down to 2^-24 relative
 constexpr SegList kSeg4 = {4, {1, 1, 0, 0}, {1, 0, 1, 0}};              // both operands exactly two planes: every term
+constexpr SegList kSeg2 = {2, {0, 0}, {1, 0}};                          // exact one-plane left operand, two-plane right
 constexpr SegList kSeg3x1 = {3, {2, 1, 0}, {0, 0, 0}};                   // 3-plane left operand, exact right operand
 
 constexpr int kResidSlots = 512;
@@ -494,7 +495,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   };
   // X' = X W (+ X): reads the planes in buffer `cur`, writes np_x planes (both layouts)
   // into the other buffer, and the fp32 iterate when asked.
-  // np_t < 0: the hand-over form -- the result rounded to two planes, that value in PX and in two planes of each layout.
+  // np_t < 0: the hand-over form -- the result rounded to -np_t planes, that value in PX and in as many planes of each layout.
   auto apply = [&](const SegList& sl, const bf16_bits* W, int np_t, int np_n, bool add_x, float* out32) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
@@ -507,6 +508,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     hipError_t e;
     if (np_t < 0) {
       g.C32 = ctx->PX;
+      g.np_out = -np_t;
       e = launch_gemm_nt(g, EPI_XLAST, h, s);
     } else {
       g.np_out = np_t; g.np_out_n = np_n;
@@ -559,7 +561,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // The singular values of X0 lie in [l, 1]; l is the value the proximal term guarantees
   // on the null space of M, halved.  (Smaller ones still grow by the factor a > 2.5 per
   // step and are finished by the closing iterations.)
-  bool two_plane_iterate = false;   // the iterate in PX is exactly the sum of the first two planes of buffer `cur`
+  int handover_planes = 0;   // 1 / 2: the iterate in PX is exactly the sum of that many planes of buffer `cur`; 0: all three
   auto main_phase = [&](double l0, bool planes_ready) -> conqur_status {
     if (!planes_ready) HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s));
     const double e_stop = np_main == 1 ? 4e-3 : 5e-4;   // the safety margins below floor the ripple near 2e-4
@@ -578,9 +580,9 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
         l = 0.98 * (1.0 - E);
         u = 1.01 * (1.0 + E);
       }
-      HIP_TRY(launch_head_polar128(ctx->PXn[cur], ctx->PXt[cur], h, sc, ctx->PX, ctx->PXn[cur ^ 1], ctx->PXt[cur ^ 1], plane, s));
+      HIP_TRY(launch_head_polar128(ctx->PXn[cur], ctx->PXt[cur], h, sc, ctx->PX, ctx->PXn[cur ^ 1], ctx->PXt[cur ^ 1], s));
       cur ^= 1;
-      two_plane_iterate = true;
+      handover_planes = 1;
       iters += sc.nsteps;
       if (trace) std::fprintf(stderr, "[conqur] polar main phase: %d steps in one launch, l0=%.3e\n", sc.nsteps, l0);
       return CONQUR_OK;
@@ -591,15 +593,16 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       const bool last = E <= e_stop || iters + 1 >= cap;
       HIP_TRY(gram(seg_main, (float)a, (float)b, np_main, trace));
       ++slot;
-      // the last main step hands over to the closing iterations: the iterate rounded to two planes (16 bits: far
-      // below the error this phase leaves), held as fp32 and as two planes of each layout, so that the closing
-      // Gram matrix X^T X is exact with 4 plane products and the correction product reads the same value
-      // (three-plane main steps keep all 24 bits: their accuracy is below that rounding)
+      // The last main step hands over to the closing iterations.  Its result is rounded to the planes this phase
+      // works with anyway (one: 8 bits, two: 16 bits -- a perturbation of the size every step of this phase
+      // leaves), and exactly that value is held as fp32 and as planes of each layout: the closing Gram matrix
+      // X^T X is then exact with 1 (4) plane products and the correction product reads an exact left operand.
+      // (Three-plane main steps keep all 24 bits: their accuracy is below any such rounding.)
       if (last && np_main == 3) {
         HIP_TRY(apply(seg_main, ctx->PW, 3, 2, false, ctx->PX));
       } else {
-        HIP_TRY(apply(seg_main, ctx->PW, last ? -1 : np_main, last ? -1 : np_main, false, nullptr));
-        if (last) two_plane_iterate = true;
+        HIP_TRY(apply(seg_main, ctx->PW, last ? -np_main : np_main, last ? -np_main : np_main, false, nullptr));
+        if (last) handover_planes = np_main;
       }
       ++iters;
       if (trace) std::fprintf(stderr, "[conqur] polar main step %d: [l,u]=[%.3e,%.3f] a=%.4f b=%.4f ripple=%.3e planes=%d\n", k, l, u, a, b, E, np_main);
@@ -635,8 +638,9 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     return CONQUR_OK;
   };
   while (true) {
-    HIP_TRY(gram(two_plane_iterate ? kSeg4 : kSeg6, 0.5f, -0.5f, 2, true));
-    two_plane_iterate = false;   // whatever follows (correction step, nudge) writes all three planes again
+    HIP_TRY(gram(handover_planes == 1 ? kSeg1 : (handover_planes == 2 ? kSeg4 : kSeg6), 0.5f, -0.5f, 2, true));
+    const SegList& seg_corr = handover_planes == 1 ? kSeg2 : kSeg3;   // the correction product X (D + 1.5 D^2)
+    handover_planes = 0;   // whatever follows (correction step, nudge) writes all three planes again
     last_slot = slot++;
     // The first check after a main phase practically always calls for the quintic step: enqueue its D^2 product
     // before the host waits for the residual, so that the device keeps working through the round trip.
@@ -676,7 +680,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       HIP_TRY(hipMemcpyAsync(ctx->PX, ctx->R, (size_t)plane * sizeof(float), hipMemcpyDeviceToDevice, s));
       final_x = ctx->PX;
     }
-    HIP_TRY(apply(kSeg3, W, lean ? 0 : 3, lean ? 0 : 2, true, lean ? ctx->R : ctx->PX));
+    HIP_TRY(apply(seg_corr, W, lean ? 0 : 3, lean ? 0 : 2, true, lean ? ctx->R : ctx->PX));
     if (lean) final_x = ctx->R;
     ++iters; ++closing;
     if (predict) {

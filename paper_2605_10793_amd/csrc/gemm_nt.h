@@ -21,9 +21,10 @@ enum GemmEpilogue : int {
   EPI_SQUARE = 5, // acc = D^2 (D symmetric, given as two planes Padd): writes acc as one bf16 plane (Pacc) and
                   // coef_g * acc + D as two split planes (Pn)
   EPI_FRO2 = 6,   // per-wavefront partial sums of acc^2 only (resid_part): a Frobenius norm, nothing stored
-  EPI_XLAST = 7,  // acc = X' rounded to two bf16 split planes (16 significant bits): exactly that value goes to C32
-                  // (fp32), to two natural planes (Pn) and to two transposed planes (Pt) -- the hand-over from the
-                  // low-precision polar steps to the closing ones, whose Gram matrix then needs 4 plane products, not 6
+  EPI_XLAST = 7,  // acc = X' rounded to np_out (1 or 2) bf16 split planes: exactly that value goes to C32 (fp32), to
+                  // np_out natural planes (Pn) and to np_out transposed planes (Pt) -- the hand-over from the
+                  // low-precision polar steps to the closing ones, whose Gram matrix is then exact with 1 or 4 plane
+                  // products instead of the 6 a 24-bit iterate needs
 };
 
 constexpr int kMaxSegments = 6;

@@ -399,6 +399,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
     if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
   } else if constexpr (EPI == EPI_XLAST) {
     const int64_t boff = (int64_t)bz * g.batchC;
+    const bool two = g.np_out == 2;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -410,28 +411,33 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           const int mb = mw + i * 32 + 8 * q + 4 * half;   // 4 consecutive rows mb .. mb+3 (M is a multiple of 4)
           if (mb >= g.M) continue;
           const float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
-          uint2 hi, lo;
+          uint2 hi;
           hi.x = f32x2_to_bf16x2(v0, v1);
           hi.y = f32x2_to_bf16x2(v2, v3);
-          const float h0 = __uint_as_float(hi.x << 16), h1 = __uint_as_float(hi.x & 0xffff0000u);
-          const float h2 = __uint_as_float(hi.y << 16), h3 = __uint_as_float(hi.y & 0xffff0000u);
-          lo.x = f32x2_to_bf16x2(v0 - h0, v1 - h1);
-          lo.y = f32x2_to_bf16x2(v2 - h2, v3 - h3);
+          float h0 = __uint_as_float(hi.x << 16), h1 = __uint_as_float(hi.x & 0xffff0000u);
+          float h2 = __uint_as_float(hi.y << 16), h3 = __uint_as_float(hi.y & 0xffff0000u);
           const int64_t off = boff + (int64_t)mb * g.ldc + n;
-          // hi + lo has at most 17 significant bits: the fp32 sum is exact
-          g.C32[off] = h0 + __uint_as_float(lo.x << 16);
-          g.C32[off + g.ldc] = h1 + __uint_as_float(lo.x & 0xffff0000u);
-          g.C32[off + 2 * g.ldc] = h2 + __uint_as_float(lo.y << 16);
-          g.C32[off + 3 * g.ldc] = h3 + __uint_as_float(lo.y & 0xffff0000u);
           bf16_bits* pn = g.Pn + off;
+          bf16_bits* pt = g.Pt + boff + (int64_t)n * g.ldc + mb;
           pn[0] = (bf16_bits)hi.x; pn[g.ldc] = (bf16_bits)(hi.x >> 16);
           pn[2 * g.ldc] = (bf16_bits)hi.y; pn[3 * g.ldc] = (bf16_bits)(hi.y >> 16);
-          pn += g.plane_out;
-          pn[0] = (bf16_bits)lo.x; pn[g.ldc] = (bf16_bits)(lo.x >> 16);
-          pn[2 * g.ldc] = (bf16_bits)lo.y; pn[3 * g.ldc] = (bf16_bits)(lo.y >> 16);
-          bf16_bits* pt = g.Pt + boff + (int64_t)n * g.ldc + mb;
           *reinterpret_cast<uint2*>(pt) = hi;
-          *reinterpret_cast<uint2*>(pt + g.plane_out) = lo;
+          if (two) {
+            uint2 lo;
+            lo.x = f32x2_to_bf16x2(v0 - h0, v1 - h1);
+            lo.y = f32x2_to_bf16x2(v2 - h2, v3 - h3);
+            pn += g.plane_out;
+            pn[0] = (bf16_bits)lo.x; pn[g.ldc] = (bf16_bits)(lo.x >> 16);
+            pn[2 * g.ldc] = (bf16_bits)lo.y; pn[3 * g.ldc] = (bf16_bits)(lo.y >> 16);
+            *reinterpret_cast<uint2*>(pt + g.plane_out) = lo;
+            // hi + lo has at most 17 significant bits: the fp32 sums are exact
+            h0 += __uint_as_float(lo.x << 16); h1 += __uint_as_float(lo.x & 0xffff0000u);
+            h2 += __uint_as_float(lo.y << 16); h3 += __uint_as_float(lo.y & 0xffff0000u);
+          }
+          g.C32[off] = h0;
+          g.C32[off + g.ldc] = h1;
+          g.C32[off + 2 * g.ldc] = h2;
+          g.C32[off + 3 * g.ldc] = h3;
         }
       }
   } else {  // EPI_XOUT
@@ -545,7 +551,7 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
       batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
     return hipErrorInvalidValue;
-  if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3))) return hipErrorInvalidValue;
+  if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
     case EPI_ACT: return launch_epi<EPI_ACT>(a, batch, stream);

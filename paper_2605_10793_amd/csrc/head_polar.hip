@@ -12,8 +12,8 @@
 // (an accumulator lane owns 4 consecutive rows of one column, i.e. 8 contiguous bytes of the
 // transposed matrix: computing the product in both orientations replaces the scattered
 // 2-byte stores a single orientation would need for its own layout).
-// The last step writes what the closing iterations read: the iterate rounded to two bf16
-// split planes, as fp32 and as two planes of each layout.
+// The last step writes what the closing iterations read: the iterate rounded to bf16, as
+// fp32 and as one plane of each layout.
 #include "kernels.h"
 
 namespace conqur {
@@ -28,7 +28,7 @@ __device__ __forceinline__ int loff(int row, int chunk) { return row * ROWB + ((
 
 __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restrict__ Xn0, const bf16_bits* __restrict__ Xt0,
                                                        const PolarSchedule sched, float* __restrict__ X32,
-                                                       bf16_bits* __restrict__ Pn, bf16_bits* __restrict__ Pt, int64_t plane) {
+                                                       bf16_bits* __restrict__ Pn, bf16_bits* __restrict__ Pt) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* const sXn = smem;                  // X   : row r, K = column
   unsigned char* const sXt = smem + DH * ROWB;      // X^T : row c, K = row of X
@@ -109,10 +109,9 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
     __syncthreads();
   }
 
-  // Hand-over to the closing iterations: the iterate rounded to two bf16 planes (16 significant bits), that value as
-  // fp32 X, as 2 transposed planes (from X') and as 2 natural planes (from X'^T): the closing Gram matrix is then exact
-  // with 4 plane products (fp32 X and the transposed planes come from the same accumulators; the natural planes, from
-  // the other orientation of the product, feed only the small correction product of the closing step).
+  // Hand-over to the closing iterations: the result rounded to bf16 like every step's, and exactly that value as fp32 X,
+  // as one transposed plane (from X') and as one natural plane (from X'^T; the two orientations issue the same products
+  // in the same order, so they hold the same numbers): the closing Gram matrix is then exact with one plane product.
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -121,32 +120,17 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int m0 = 64 * wm + 32 * i + 8 * jj + 4 * half;
-        float v[4], t[4];
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-          v[ii] = acc[i][j][4 * jj + ii];
-          t[ii] = accT[i][j][4 * jj + ii];
-        }
-        uint2 hi, lo;
-        hi.x = f32x2_to_bf16x2(v[0], v[1]);
-        hi.y = f32x2_to_bf16x2(v[2], v[3]);
-        const float h[4] = {__uint_as_float(hi.x << 16), __uint_as_float(hi.x & 0xffff0000u), __uint_as_float(hi.y << 16),
-                            __uint_as_float(hi.y & 0xffff0000u)};
-        lo.x = f32x2_to_bf16x2(v[0] - h[0], v[1] - h[1]);
-        lo.y = f32x2_to_bf16x2(v[2] - h[2], v[3] - h[3]);
-        const float l[4] = {__uint_as_float(lo.x << 16), __uint_as_float(lo.x & 0xffff0000u), __uint_as_float(lo.y << 16),
-                            __uint_as_float(lo.y & 0xffff0000u)};
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) X32[hoff + (int64_t)(m0 + ii) * DH + n] = h[ii] + l[ii];   // exact: <= 17 bits
-        *reinterpret_cast<uint2*>(Pt + hoff + (int64_t)n * DH + m0) = hi;            // X^T[c = n][r = m0 ..]
-        *reinterpret_cast<uint2*>(Pt + plane + hoff + (int64_t)n * DH + m0) = lo;
-        uint2 thi, tlo;
-        thi.x = f32x2_to_bf16x2(t[0], t[1]);
-        thi.y = f32x2_to_bf16x2(t[2], t[3]);
-        tlo.x = f32x2_to_bf16x2(t[0] - __uint_as_float(thi.x << 16), t[1] - __uint_as_float(thi.x & 0xffff0000u));
-        tlo.y = f32x2_to_bf16x2(t[2] - __uint_as_float(thi.y << 16), t[3] - __uint_as_float(thi.y & 0xffff0000u));
-        *reinterpret_cast<uint2*>(Pn + hoff + (int64_t)n * DH + m0) = thi;           // accT: X[r = n][c = m0 ..]
-        *reinterpret_cast<uint2*>(Pn + plane + hoff + (int64_t)n * DH + m0) = tlo;
+        uint2 hi, thi;
+        hi.x = f32x2_to_bf16x2(acc[i][j][4 * jj], acc[i][j][4 * jj + 1]);
+        hi.y = f32x2_to_bf16x2(acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]);
+        thi.x = f32x2_to_bf16x2(accT[i][j][4 * jj], accT[i][j][4 * jj + 1]);
+        thi.y = f32x2_to_bf16x2(accT[i][j][4 * jj + 2], accT[i][j][4 * jj + 3]);
+        X32[hoff + (int64_t)m0 * DH + n] = __uint_as_float(hi.x << 16);
+        X32[hoff + (int64_t)(m0 + 1) * DH + n] = __uint_as_float(hi.x & 0xffff0000u);
+        X32[hoff + (int64_t)(m0 + 2) * DH + n] = __uint_as_float(hi.y << 16);
+        X32[hoff + (int64_t)(m0 + 3) * DH + n] = __uint_as_float(hi.y & 0xffff0000u);
+        *reinterpret_cast<uint2*>(Pt + hoff + (int64_t)n * DH + m0) = hi;     // X^T[c = n][r = m0 ..]
+        *reinterpret_cast<uint2*>(Pn + hoff + (int64_t)n * DH + m0) = thi;    // accT: X[r = n][c = m0 ..]
       }
     }
 }
@@ -154,7 +138,7 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
 }  // namespace
 
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
-                                bf16_bits* Pn, bf16_bits* Pt, int64_t plane, hipStream_t s) {
+                                bf16_bits* Pn, bf16_bits* Pt, hipStream_t s) {
   if (heads < 1 || sched.nsteps < 1 || sched.nsteps > kPolarScheduleMax) return hipErrorInvalidValue;
   static PerDeviceOnce configured;
   hipError_t e = configured.run([] {
@@ -162,7 +146,7 @@ hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int 
                                kSmemBytes);
   });
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_head_polar128, dim3(heads), dim3(256), kSmemBytes, s, Xn0, Xt0, sched, X32, Pn, Pt, plane);
+  hipLaunchKernelGGL(k_head_polar128, dim3(heads), dim3(256), kSmemBytes, s, Xn0, Xt0, sched, X32, Pn, Pt);
   return hipGetLastError();
 }
 

@@ -70,14 +70,14 @@ hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* 
 // Main phase of the polar iteration for heads of width 128 in one launch (head_polar.hip): runs the composed cubics
 // X <- X (a_k I + b_k X^T X), k < nsteps, on single bf16 operand planes held in LDS.  Xn0 / Xt0: the start iterate as
 // one natural and one transposed bf16 plane [heads][128][128].  Outputs, as the last step of the general path writes them:
-// X32 (fp32 iterate), Pt (3 transposed split planes), Pn (2 natural split planes), planes `plane` elements apart.
+// the result rounded to bf16, as X32 (fp32), Pt (one transposed plane) and Pn (one natural plane).
 constexpr int kPolarScheduleMax = 64;
 struct PolarSchedule {
   int nsteps;
   float a[kPolarScheduleMax], b[kPolarScheduleMax];
 };
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
-                                bf16_bits* Pn, bf16_bits* Pt, int64_t plane, hipStream_t s);
+                                bf16_bits* Pn, bf16_bits* Pt, hipStream_t s);
 
 // Per-row fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse / row_en, then their sums over rows:
 // out[0] = SSE, out[1] = energy (skipped if out is null).  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
