@@ -92,6 +92,8 @@ struct conqur_ctx {
   int clk_wg[2] = {0, 0};                            // workgroups that wrote them in the last step (0: none)
   hipEvent_t ev[ST_COUNT][2]{};
   bool ev_valid[ST_COUNT]{};
+  hipEvent_t ev_resid = nullptr;   // behind the copy of a closing residual: the host waits for this, not for the stream
+  double* host_res = nullptr;      // pinned: [kResidSlots][heads] residual history, then the update's result block
   std::vector<void*> allocs;
 };
 
@@ -181,6 +183,8 @@ void conqur_destroy(conqur_ctx* ctx) {
   for (int s = 0; s < ST_COUNT; ++s)
     for (int k = 0; k < 2; ++k)
       if (ctx->ev[s][k]) (void)hipEventDestroy(ctx->ev[s][k]);
+  if (ctx->ev_resid) (void)hipEventDestroy(ctx->ev_resid);
+  if (ctx->host_res) (void)hipHostFree(ctx->host_res);
   delete ctx;
 }
 
@@ -228,10 +232,14 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   ctx->rows = reinterpret_cast<unsigned long long*>(ctx->L + ctx->heads);
   ctx->skipped = ctx->rows + ctx->heads;
   ctx->cnt = ctx->skipped + ctx->heads;
-  A(dev_alloc(ctx, &ctx->ldot, (size_t)ctx->heads));
+  // the update's scalar results share one allocation (one copy brings them to the host):
+  // <R_op, M> | <R, M> | ||M||_F^2 per head, then the non-finite flag
+  A(dev_alloc(ctx, &ctx->ldot, (size_t)3 * ctx->heads + 1));
+  ctx->inner = ctx->ldot + ctx->heads;
+  ctx->fro2 = ctx->inner + ctx->heads;
+  ctx->nonfinite = reinterpret_cast<int*>(ctx->fro2 + ctx->heads);
   A(dev_alloc(ctx, &ctx->dotrm_part, (size_t)ctx->heads * dot_rm_partials((int64_t)dh * dh)));
   ctx->l_base.assign(ctx->heads, 0.0);
-  A(dev_alloc(ctx, &ctx->nonfinite, (size_t)4));
   A(dev_alloc(ctx, reinterpret_cast<char**>(&ctx->Y), tmax * d * (ctx->f32 ? 4 : 2)));
   A(dev_alloc(ctx, &ctx->row_sse, 2 * tmax));   // per-row SSE, then per-row energy
   ctx->row_en = ctx->row_sse + tmax;
@@ -252,11 +260,13 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
     A(dev_alloc(ctx, &ctx->Mpart, (size_t)ctx->head_splits * blk));
   }
   A(dev_alloc(ctx, &ctx->dot_part, (size_t)ctx->heads * pack_dot_partials(ctx->dh)));
-  A(dev_alloc(ctx, &ctx->fro2, (size_t)ctx->heads));
-  A(dev_alloc(ctx, &ctx->inner, (size_t)ctx->heads));
   for (int k = 0; k < 2; ++k) A(dev_alloc(ctx, &ctx->clk[k], (size_t)4 * kClkMaxWorkgroups));
   for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
     for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreate(&ctx->ev[s][k]);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_resid, hipEventDisableTiming);
+  if (e == hipSuccess)
+    e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_res), ((size_t)kResidSlots * ctx->heads + 3 * ctx->heads + 1) * sizeof(double),
+                      hipHostMallocDefault);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->R, R0_host, blk * sizeof(float), hipMemcpyHostToDevice, ctx->stream);
   if (e == hipSuccess) e = launch_pack(ctx->R, ctx->heads, ctx->dh, ctx->dh, ctx->np, nullptr, ctx->RopT, (int64_t)blk, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
@@ -546,11 +556,15 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     if (e == hipSuccess) e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);
     return e;
   };
-  std::vector<double> hist((size_t)kResidSlots * h);
-  auto read_resid = [&](int sl_idx, double* worst) -> conqur_status {
-    HIP_TRY(hipMemcpyAsync(hist.data() + (size_t)sl_idx * h, ctx->resid + (size_t)sl_idx * h, h * sizeof(double),
-                           hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
+  double* const hist = ctx->host_res;   // pinned, so that the copies below are asynchronous
+  // The copy of residual slot sl_idx and an event behind it; work enqueued after this does not delay the host's read.
+  auto post_resid = [&](int sl_idx) -> conqur_status {
+    HIP_TRY(hipMemcpyAsync(hist + (size_t)sl_idx * h, ctx->resid + (size_t)sl_idx * h, h * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipEventRecord(ctx->ev_resid, s));
+    return CONQUR_OK;
+  };
+  auto wait_resid = [&](int sl_idx, double* worst) -> conqur_status {
+    HIP_TRY(hipEventSynchronize(ctx->ev_resid));
     double w = 0.0;
     for (int q = 0; q < h; ++q) w = std::max(w, std::sqrt(hist[(size_t)sl_idx * h + q]));
     *worst = w;
@@ -645,8 +659,10 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     // The first check after a main phase practically always calls for the quintic step: enqueue its D^2 product
     // before the host waits for the residual, so that the device keeps working through the round trip.
     const bool spec_square = closing == 0;
+    st = post_resid(last_slot);   // before the D^2 product, so that the host reads the residual while that runs
+    if (st != CONQUR_OK) return st;
     if (spec_square) HIP_TRY(square_correction(keep_sq));
-    st = read_resid(last_slot, &res);
+    st = wait_resid(last_slot, &res);
     if (st != CONQUR_OK) return st;
     if (trace) std::fprintf(stderr, "[conqur] polar closing check: resid_F=%.6e (iters %u)\n", res, iters);
     if (!std::isfinite(res)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
@@ -691,13 +707,15 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       // calibrated against the measured residual).
       HIP_TRY(cube_norm());
       const int cslot = slot++;
+      st = post_resid(cslot);
+      if (st != CONQUR_OK) return st;
       if (lean) {   // expected to be the end: the finishing kernels go in before the host waits for the norm
         st = enqueue_finish();
         if (st != CONQUR_OK) return st;
         finished = true;
       }
       double d3 = 0.0;
-      st = read_resid(cslot, &d3);
+      st = wait_resid(cslot, &d3);
       if (st != CONQUR_OK) return st;
       const double pred = kCubeFactor * d3 + kOrthFloorPerDim * dh;
       if (trace) std::fprintf(stderr, "[conqur] polar closing: ||D^3||_F=%.4e predicted resid_F=%.4e\n", d3, pred);
@@ -723,14 +741,14 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     if (st != CONQUR_OK) return st;
   }
   ctx->ev_valid[ST_UPDATE] = timed;
-  int nonfinite = 0;
-  std::vector<double> inner(h), fro2(h), ldot(h);
-  HIP_TRY(hipMemcpyAsync(ldot.data(), ctx->ldot, h * sizeof(double), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipMemcpyAsync(inner.data(), ctx->inner, h * sizeof(double), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipMemcpyAsync(fro2.data(), ctx->fro2, h * sizeof(double), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipMemcpyAsync(&nonfinite, ctx->nonfinite, sizeof(int), hipMemcpyDeviceToHost, s));
+  // <R_op, M> | <R, M> | ||M||_F^2 | non-finite flag: one copy of the result block
+  double* const resblk = ctx->host_res + (size_t)kResidSlots * h;
+  HIP_TRY(hipMemcpyAsync(resblk, ctx->ldot, ((size_t)3 * h + 1) * sizeof(double), hipMemcpyDeviceToHost, s));
   HIP_TRY(launch_fill_zero(ctx->nonfinite, sizeof(int), s));
   HIP_TRY(hipStreamSynchronize(s));
+  const double *ldot = resblk, *inner = resblk + h, *fro2 = resblk + 2 * h;
+  int nonfinite = 0;
+  std::memcpy(&nonfinite, resblk + 3 * h, sizeof(int));
   ctx->m_empty = true;
   ctx->have_rows = false;
   if (out) {
