@@ -33,8 +33,8 @@ constexpr int kResidSlots = 512;
 // operands, fp32 iterate): used where the residual is predicted instead of measured.
 constexpr double kOrthFloorPerDim = 1e-8;
 constexpr double kCubeFactor = 5.5;
-constexpr int kClkMaxWorkgroups = 8192;
-constexpr int64_t kHostSumRows = 16384;   // quant_error: up to this many rows the host adds the per-row results   // clock probes are taken for GEMM launches of at most this many workgroups
+constexpr int kClkMaxWorkgroups = 8192;    // clock probes are taken for GEMM launches of at most this many workgroups
+constexpr int64_t kHostSumRows = 16384;    // quant_error: up to this many rows the host adds the per-row results
 
 enum Stage { ST_PREP = 0, ST_ROTATE, ST_ACCUM, ST_STATS, ST_UPDATE, ST_QROT, ST_QERR, ST_STEP, ST_QUANT, ST_COUNT };
 constexpr int kTimingSlots = 12;
@@ -94,6 +94,7 @@ struct conqur_ctx {
   bool ev_valid[ST_COUNT]{};
   hipEvent_t ev_resid = nullptr;   // behind the copy of a closing residual: the host waits for this, not for the stream
   double* host_res = nullptr;      // pinned: [kResidSlots][heads] residual history, then the update's result block
+  float* host_rows = nullptr;      // pinned: per-row errors and energies of one score call (up to kHostSumRows rows)
   std::vector<void*> allocs;
 };
 
@@ -185,6 +186,7 @@ void conqur_destroy(conqur_ctx* ctx) {
       if (ctx->ev[s][k]) (void)hipEventDestroy(ctx->ev[s][k]);
   if (ctx->ev_resid) (void)hipEventDestroy(ctx->ev_resid);
   if (ctx->host_res) (void)hipHostFree(ctx->host_res);
+  if (ctx->host_rows) (void)hipHostFree(ctx->host_rows);
   delete ctx;
 }
 
@@ -266,6 +268,9 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_resid, hipEventDisableTiming);
   if (e == hipSuccess)
     e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_res), ((size_t)kResidSlots * ctx->heads + 3 * ctx->heads + 1) * sizeof(double),
+                      hipHostMallocDefault);
+  if (e == hipSuccess)
+    e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_rows), (size_t)2 * std::min<size_t>(tmax, kHostSumRows) * sizeof(float),
                       hipHostMallocDefault);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->R, R0_host, blk * sizeof(float), hipMemcpyHostToDevice, ctx->stream);
   if (e == hipSuccess) e = launch_pack(ctx->R, ctx->heads, ctx->dh, ctx->dh, ctx->np, nullptr, ctx->RopT, (int64_t)blk, ctx->stream);
@@ -791,15 +796,15 @@ static conqur_status quant_error_impl(conqur_ctx* ctx, const void* X, uint64_t T
   {
     StageTimer tm(ctx, ST_QERR);
     // a batch's per-row results are small: the host adds them (fixed order) instead of one more kernel launch
-    HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, zero_point, clip, ctx->row_sse, ctx->row_en,
+    // (the per-row energies directly behind the per-row errors: one copy brings both)
+    HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, zero_point, clip, ctx->row_sse, ctx->row_sse + T,
                                T <= kHostSumRows ? nullptr : ctx->qsum, nullptr, 0, s));
   }
   }
   double host[2] = {0.0, 0.0};
   if (T <= kHostSumRows) {
-    std::vector<float> rows((size_t)2 * T);
-    HIP_TRY(hipMemcpyAsync(rows.data(), ctx->row_sse, T * sizeof(float), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(rows.data() + T, ctx->row_en, T * sizeof(float), hipMemcpyDeviceToHost, s));
+    const float* rows = ctx->host_rows;   // pinned
+    HIP_TRY(hipMemcpyAsync(ctx->host_rows, ctx->row_sse, (size_t)2 * T * sizeof(float), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     for (int64_t i = 0; i < T; ++i) { host[0] += (double)rows[i]; host[1] += (double)rows[T + i]; }
   } else {
