@@ -442,6 +442,22 @@ def test_error_paths(B):
         with pytest.raises(B.ConqurError) as e:
             cal.quant_error(X[:8], bits=9)
         assert e.value.status == B.EINVAL
+        for kw in (dict(bits=1), dict(bits=4, clip_ratio=0.0), dict(bits=4, clip_ratio=1.5)):
+            with pytest.raises(B.ConqurError) as e:
+                cal.rotate_quant(X[:8], **kw)
+            assert e.value.status == B.EINVAL, kw
+        with pytest.raises(B.ConqurError) as e:
+            cal.quant_error_zp(X[:8], 4, 0.0)
+        assert e.value.status == B.EINVAL
+        Yq = torch.zeros(8, 72, dtype=torch.bfloat16, device="cuda:0")
+        with pytest.raises(B.ConqurError) as e:                                     # output rows not 16-byte aligned
+            cal.rotate_quant(X[:7], 4, True, 1.0, Yq.view(-1)[4:4 + 7 * 72].view(7, 72)[:, :64])
+        assert e.value.status == B.EINVAL
+        with pytest.raises(ValueError):
+            cal.rotate(X[:8], torch.zeros(8, 32, dtype=torch.bfloat16, device="cuda:0"))   # output narrower than d
+        with pytest.raises(B.ConqurError) as e:
+            cal.last_corners(8)                                                     # no step yet
+        assert e.value.status == B.ESTATE
         w = I.small_workload(64, 32, seed=3)
         cal.step_batch(B.to_device(I.batch(w, 0), "bf16"))
         rc, st = cal.update_rotation(allow=(B.ENOCONV,))                           # cap of 1 iteration
