@@ -502,6 +502,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.nseg = sl.n;
     for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * plane; g.b_seg[q] = sl.b[q] * plane; }
     g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW; g.np_out = np_w; g.plane_out = plane;
+    g.symmetric = 1;   // X^T X: tiles above the diagonal are computed once and stored twice
     g.resid_part = want_resid ? ctx->resid_part : nullptr; g.coef_i = ci; g.coef_g = cg;
     hipError_t e = launch_gemm_nt(g, EPI_GRAMW, h, s);
     if (e == hipSuccess && want_resid)
@@ -543,6 +544,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.nseg = 1;   // D^2 is second order small: single bf16 planes are ample
     g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW2; g.np_out = 2; g.plane_out = plane;
     g.Padd = ctx->PW; g.np_add = 2; g.coef_i = 0.0f; g.coef_g = 1.5f;
+    g.symmetric = 1;
     if (!keep_square) return launch_gemm_nt(g, EPI_GRAMW, h, s);
     g.Pacc = ctx->PW2 + 2 * plane;   // D^2 itself, third plane of the buffer
     return launch_gemm_nt(g, EPI_SQUARE, h, s);

@@ -45,8 +45,9 @@ __device__ __forceinline__ void pipeline_barrier() { asm volatile("s_barrier" ::
 // the hardware returns zeros (also for loads whose destination is LDS).
 constexpr uint32_t kOobOffset = 0x80000000u;
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16, bool SYM>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs g, const int tiles_m, const int tiles_n) {
+  static_assert(!SYM || (BM == BN && (EPI == EPI_GRAMW || EPI == EPI_SQUARE)), "mirrored tiles: square tiles, symmetric results");
   constexpr int NW = WGM * WGN;                 // wavefronts per workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int NLA = BM / 8, NLB = BN / 8;     // wave-wide 1 KiB loads per stage (8 tile rows each)
@@ -71,7 +72,22 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   int bid = blockIdx.x;
   const int ntiles = tiles_m * tiles_n;
   int tm, tn;
-  if ((tiles_m & 3) == 0 && (tiles_n & 7) == 0 && (((tiles_m >> 2) * (tiles_n >> 3)) & 7) == 0) {
+  if constexpr (SYM) {
+    // Tiles on and above the diagonal only: tile rows r and T-1-r together hold T+1 of them, and such a pair of rows
+    // needs few operand panels (2 of A, T-r of B).  With T a multiple of 16 every XCD (bid % 8) gets whole pairs.
+    const int T = tiles_m;
+    int pair, within;
+    if ((T & 15) == 0) {
+      const int xcd = bid & 7, local = bid >> 3;
+      pair = xcd + 8 * (local / (T + 1));
+      within = local % (T + 1);
+    } else {
+      pair = bid / (T + 1);
+      within = bid % (T + 1);
+    }
+    if (within < T - pair) { tm = pair; tn = pair + within; }
+    else { tm = T - 1 - pair; tn = tm + (within - (T - pair)); }
+  } else if ((tiles_m & 3) == 0 && (tiles_n & 7) == 0 && (((tiles_m >> 2) * (tiles_n >> 3)) & 7) == 0) {
     const int xcd = bid & 7, local = bid >> 3;
     const int group = (local >> 5) * 8 + xcd, within = local & 31;
     const int gm = tiles_m >> 2;
@@ -328,6 +344,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
       }
   } else if constexpr (EPI == EPI_GRAMW) {
     const int64_t boff = (int64_t)bz * g.batchC;
+    [[maybe_unused]] const bool mirror = SYM && tm != tn;   // this tile is also the transpose of tile (tn, tm)
     double rsum = 0.0;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -337,29 +354,48 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         if (n >= g.N) continue;
         float part = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m >= g.M) continue;
-          const float eye = (m == n) ? 1.0f : 0.0f;
-          const float r = acc[i][j][e] - eye;
-          part += r * r;
-          float w = g.coef_i * eye + g.coef_g * acc[i][j][e];
-          const int64_t off = boff + (int64_t)m * g.ldc + n;
-          for (int p = 0; p < g.np_add; ++p) w += bf16_to_f32(g.Padd[p * g.plane_out + off]);
+        for (int q = 0; q < 4; ++q) {
+          const int mb = mw + i * 32 + 8 * q + 4 * half;   // rows mb .. mb + 3 (M is a multiple of 4)
+          if (mb >= g.M) continue;
+          float w[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float a = acc[i][j][4 * q + r];
+            const float eye = (mb + r == n) ? 1.0f : 0.0f;
+            const float d = a - eye;
+            part += d * d;
+            w[r] = g.coef_i * eye + g.coef_g * a;
+            const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
+            for (int p = 0; p < g.np_add; ++p) w[r] += bf16_to_f32(g.Padd[p * g.plane_out + off]);
+          }
           for (int p = 0; p < g.np_out; ++p) {
-            const bf16_bits hb = f32_to_bf16(w);
-            g.Pn[p * g.plane_out + off] = hb;
-            w -= bf16_to_f32(hb);
+            uint2 t;
+            t.x = f32x2_to_bf16x2(w[0], w[1]);
+            t.y = f32x2_to_bf16x2(w[2], w[3]);
+            w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
+            w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
+            bf16_bits* pn = g.Pn + p * g.plane_out + boff + (int64_t)mb * g.ldc + n;
+            pn[0] = (bf16_bits)t.x; pn[g.ldc] = (bf16_bits)(t.x >> 16);
+            pn[2 * g.ldc] = (bf16_bits)t.y; pn[3 * g.ldc] = (bf16_bits)(t.y >> 16);
+            if constexpr (SYM) {
+              if (mirror) *reinterpret_cast<uint2*>(g.Pn + p * g.plane_out + boff + (int64_t)n * g.ldc + mb) = t;
+            }
           }
         }
         rsum += (double)part;
       }
     if (g.resid_part) {
       rsum = wave_sum_d(rsum);
-      if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+      if (lane == 0) {
+        g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+        if constexpr (SYM) {   // the mirrored tile's slot: the sum over all slots stays the sum over the whole matrix
+          if (mirror) g.resid_part[((int64_t)bz * ntiles + tm * tiles_m + tn) * NW + wave] = rsum;
+        }
+      }
     }
   } else if constexpr (EPI == EPI_SQUARE) {
     const int64_t boff = (int64_t)bz * g.batchC;
+    [[maybe_unused]] const bool mirror = SYM && tm != tn;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -367,16 +403,39 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         const int n = nw + j * 32 + col;
         if (n >= g.N) continue;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m >= g.M) continue;
-          const int64_t off = boff + (int64_t)m * g.ldc + n;
-          const float a = acc[i][j][e];
-          g.Pacc[off] = f32_to_bf16(a);
-          float w = g.coef_g * a + bf16_to_f32(g.Padd[off]) + bf16_to_f32(g.Padd[g.plane_out + off]);
-          const bf16_bits h0 = f32_to_bf16(w);
-          g.Pn[off] = h0;
-          g.Pn[g.plane_out + off] = f32_to_bf16(w - bf16_to_f32(h0));
+        for (int q = 0; q < 4; ++q) {
+          const int mb = mw + i * 32 + 8 * q + 4 * half;
+          if (mb >= g.M) continue;
+          float a[4], w[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
+            a[r] = acc[i][j][4 * q + r];
+            w[r] = g.coef_g * a[r] + bf16_to_f32(g.Padd[off]) + bf16_to_f32(g.Padd[g.plane_out + off]);
+          }
+          uint2 ta, t0, t1;
+          ta.x = f32x2_to_bf16x2(a[0], a[1]);
+          ta.y = f32x2_to_bf16x2(a[2], a[3]);
+          t0.x = f32x2_to_bf16x2(w[0], w[1]);
+          t0.y = f32x2_to_bf16x2(w[2], w[3]);
+          t1.x = f32x2_to_bf16x2(w[0] - __uint_as_float(t0.x << 16), w[1] - __uint_as_float(t0.x & 0xffff0000u));
+          t1.y = f32x2_to_bf16x2(w[2] - __uint_as_float(t0.y << 16), w[3] - __uint_as_float(t0.y & 0xffff0000u));
+          const int64_t off = boff + (int64_t)mb * g.ldc + n;
+          auto rows4 = [&](bf16_bits* base, const uint2& t) {
+            base[0] = (bf16_bits)t.x; base[g.ldc] = (bf16_bits)(t.x >> 16);
+            base[2 * g.ldc] = (bf16_bits)t.y; base[3 * g.ldc] = (bf16_bits)(t.y >> 16);
+          };
+          rows4(g.Pacc + off, ta);
+          rows4(g.Pn + off, t0);
+          rows4(g.Pn + g.plane_out + off, t1);
+          if constexpr (SYM) {
+            if (mirror) {
+              const int64_t offt = boff + (int64_t)n * g.ldc + mb;
+              *reinterpret_cast<uint2*>(g.Pacc + offt) = ta;
+              *reinterpret_cast<uint2*>(g.Pn + offt) = t0;
+              *reinterpret_cast<uint2*>(g.Pn + g.plane_out + offt) = t1;
+            }
+          }
         }
       }
   } else if constexpr (EPI == EPI_FRO2) {
@@ -506,24 +565,40 @@ int pick_tile(int M, int N, int batch) {
   return best;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16, bool SYM = false>
 hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
   static_assert(smem <= 160 * 1024, "LDS of one CU");
   static PerDeviceOnce configured;
-  auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, NSTAGE, EPI, F16>;
+  auto kern = gemm_nt_kernel<BM, BN, WGM, WGN, NSTAGE, EPI, F16, SYM>;
   hipError_t e = configured.run([&] {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   });
   if (e != hipSuccess) return e;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  dim3 grid(tiles_m * tiles_n, 1, batch);
+  dim3 grid(SYM ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n, 1, batch);
   hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), smem, stream, a, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
+constexpr int kSymMinTiles = 8;   // tiles per side from which the mirrored form is used
+
 template <int EPI, bool F16 = false>
 hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
+  if constexpr (EPI == EPI_GRAMW || EPI == EPI_SQUARE) {
+    if (a.symmetric) {   // tiles on and above the diagonal only, where the chosen tile is square and there are enough
+      const int t = pick_tile(a.M, a.N, batch);
+      if (kTiles[t].bm == kTiles[t].bn && (a.M + kTiles[t].bm - 1) / kTiles[t].bm >= kSymMinTiles) {
+        switch (t) {
+          case 0: return launch_one<256, 256, 2, 4, 2, EPI, F16, true>(a, batch, stream);
+          case 2: return launch_one<128, 128, 2, 2, 3, EPI, F16, true>(a, batch, stream);
+          case 4: return launch_one<192, 192, 3, 2, 3, EPI, F16, true>(a, batch, stream);
+          case 3: return launch_one<64, 64, 2, 2, 3, EPI, F16, true>(a, batch, stream);
+          default: break;
+        }
+      }
+    }
+  }
   switch (pick_tile(a.M, a.N, batch)) {
     // LDS stages: as many 64-deep tiles as fit (two of 64 KiB for 256 x 256; smaller tiles take a third, which
     // puts two K steps instead of one between a load's issue and its use)
@@ -550,6 +625,8 @@ int gemm_num_workgroups(int M, int N, int batch) {
 hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStream_t stream) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
       batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
+    return hipErrorInvalidValue;
+  if (a.symmetric && ((epi != EPI_GRAMW && epi != EPI_SQUARE) || a.A != a.B || a.M != a.N || a.lda != a.ldb || (a.M & 3)))
     return hipErrorInvalidValue;
   if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
