@@ -558,6 +558,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.M = g.N = g.K = dh;
     g.nseg = 1;
     g.ldc = dh; g.batchC = blk; g.plane_out = plane;
+    g.symmetric = 1;   // D and D^2 commute: D^3 is symmetric (up to the planes' rounding, which this estimate absorbs)
     g.resid_part = ctx->resid_part;
     hipError_t e = launch_gemm_nt(g, EPI_FRO2, h, s);
     if (e == hipSuccess) e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);

@@ -61,7 +61,8 @@ struct GemmArgs {
   const float* Xadd;       // EPI_XOUT: fp32 [m][n] added to acc before writing (may be null)
   bf16_bits* Pacc;         // EPI_SQUARE: the accumulator itself as one bf16 plane [m][n]
   int symmetric;           // EPI_GRAMW / EPI_SQUARE, A and B the same matrix (so M == N and the result is symmetric):
-                           // only the tiles on and above the diagonal are computed, each also stored mirrored.  With
+                           // only the tiles on and above the diagonal are computed, each also stored mirrored
+                           // (EPI_FRO2: A, B two commuting symmetric matrices; tiles above the diagonal count twice).  With
                            // half the workgroups the chip's power limit allows a higher clock: at 4096^3 the
                            // launch takes 0.8 of the full one's time; with more tiles than CUs it saves tile rounds.
                            // Used when the chosen tile is square and there are at least 8 tiles per side.

@@ -47,7 +47,8 @@ constexpr uint32_t kOobOffset = 0x80000000u;
 
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16, bool SYM>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs g, const int tiles_m, const int tiles_n) {
-  static_assert(!SYM || (BM == BN && (EPI == EPI_GRAMW || EPI == EPI_SQUARE)), "mirrored tiles: square tiles, symmetric results");
+  static_assert(!SYM || (BM == BN && (EPI == EPI_GRAMW || EPI == EPI_SQUARE || EPI == EPI_FRO2)),
+                "mirrored tiles: square tiles, symmetric results");
   constexpr int NW = WGM * WGN;                 // wavefronts per workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int NLA = BM / 8, NLB = BN / 8;     // wave-wide 1 KiB loads per stage (8 tile rows each)
@@ -455,7 +456,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         rsum += (double)part;
       }
     rsum = wave_sum_d(rsum);
-    if (lane == 0) g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+    if (lane == 0) {
+      g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+      if constexpr (SYM) {   // a tile above the diagonal stands for its mirror image as well
+        if (tm != tn) g.resid_part[((int64_t)bz * ntiles + tm * tiles_m + tn) * NW + wave] = rsum;
+      }
+    }
   } else if constexpr (EPI == EPI_XLAST) {
     const int64_t boff = (int64_t)bz * g.batchC;
     const bool two = g.np_out == 2;
@@ -585,7 +591,7 @@ constexpr int kSymMinTiles = 8;   // tiles per side from which the mirrored form
 
 template <int EPI, bool F16 = false>
 hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
-  if constexpr (EPI == EPI_GRAMW || EPI == EPI_SQUARE) {
+  if constexpr (EPI == EPI_GRAMW || EPI == EPI_SQUARE || EPI == EPI_FRO2) {
     if (a.symmetric) {   // tiles on and above the diagonal only, where the chosen tile is square and there are enough
       const int t = pick_tile(a.M, a.N, batch);
       if (kTiles[t].bm == kTiles[t].bn && (a.M + kTiles[t].bm - 1) / kTiles[t].bm >= kSymMinTiles) {
@@ -626,7 +632,8 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
       batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
     return hipErrorInvalidValue;
-  if (a.symmetric && ((epi != EPI_GRAMW && epi != EPI_SQUARE) || a.A != a.B || a.M != a.N || a.lda != a.ldb || (a.M & 3)))
+  if (a.symmetric && ((epi != EPI_GRAMW && epi != EPI_SQUARE && epi != EPI_FRO2) || (epi != EPI_FRO2 && a.A != a.B) ||
+                      a.M != a.N || a.lda != a.ldb || (a.M & 3)))
     return hipErrorInvalidValue;
   if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
