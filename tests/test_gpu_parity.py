@@ -559,9 +559,11 @@ def test_zero_point_quantiser_closed_forms(B):
         cal.close()
 
 
-def test_planted_polar_large(B):
-    """A = Q P (P SPD, prescribed spectrum): polar(A) = Q at a size where the Jacobi oracle is slow."""
-    d = 1024
+@pytest.mark.parametrize("d", [1024, 1168, 2832])
+def test_planted_polar_large(B, d):
+    """A = Q P (P SPD, prescribed spectrum): polar(A) = Q at sizes where the Jacobi oracle is slow.  1168 and 2832 are
+    not multiples of any tile: the symmetric products of the iteration (tiles on and above the diagonal, stored
+    mirrored) then have ragged tiles on the last tile row and column, with an odd and an even tile count per side."""
     Q = I.random_orthogonal(d, 41)
     sig = np.logspace(0, -4, d)
     P, _ = I.spd_with_spectrum(d, sig, 42)
