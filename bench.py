@@ -72,8 +72,9 @@ def main():
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path is single-device; see DESIGN.md for how it would "
-              "shard); --gpus N with N > 1 is not supported", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path is single-device; sharded, every GPU would accumulate "
+              "its own M over its tokens and all-reduce it before the update); --gpus N with N > 1 is not supported",
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
