@@ -195,8 +195,9 @@ def main():
         "roofline_polar": {
             "bound": "mfma", "achieved": polar_flops / (acc["update"] * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": polar_flops / (acc["update"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            "note": "algorithmic 4*d^3 per Newton-Schulz iteration over the whole update (split-precision "
-                    "iterations issue 6x the MFMA work of a bf16 one)",
+            "note": "algorithmic 4*d^3 per polar iteration (one Gram matrix, one apply) over the whole update; the "
+                    "MFMA work actually issued differs: symmetric products run on the tiles on and above the "
+                    "diagonal only, the closing step adds the D^2, ||D^3|| and two-plane correction products",
         },
         "roofline_quant_error": {
             "bound": "hbm", "achieved": y_bytes / (acc["quant_error"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
