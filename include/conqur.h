@@ -111,6 +111,21 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
 conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems);
 
 /*
+ * The same for the heads [head0, head0 + nheads) only: X_dev holds T rows whose first
+ * nheads * dh columns belong to those heads.  One context can so carry the per-head
+ * rotations of several layers (Alg. 1 keeps one R_2 per layer, App. A one block per
+ * head): every layer's batch goes to its own range, and a single
+ * conqur_update_rotation then updates all of them in batched launches that fill the
+ * device, which one layer's heads alone do not.  A partial range needs heads of width
+ * 128 and bf16 activations (CONQUR_EINVAL otherwise); the full range is
+ * conqur_step_batch.  Every head must have received rows before the update
+ * (CONQUR_ESTATE otherwise).  After a partial range conqur_get_last_corners has nothing
+ * to return (CONQUR_ESTATE).
+ */
+conqur_status conqur_step_batch_heads(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems,
+                                      uint32_t head0, uint32_t nheads);
+
+/*
  * Read the per-head statistics accumulated since the last update.  stats_host:
  * HOST array of `heads` entries.  Synchronises the stream.
  */

@@ -21,7 +21,7 @@ STATUS_NAMES = ["OK", "EINVAL", "ESTATE", "ENOMEM", "EHIP", "ENOCONV", "ENONFINI
 F32, BF16 = 0, 1
 
 EXPORTS = [
-    "conqur_init", "conqur_step_batch", "conqur_get_batch_stats", "conqur_update_rotation",
+    "conqur_init", "conqur_step_batch", "conqur_step_batch_heads", "conqur_get_batch_stats", "conqur_update_rotation",
     "conqur_quant_error", "conqur_quant_error_zp", "conqur_rotate", "conqur_rotate_quant", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
     "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
@@ -65,6 +65,8 @@ def load() -> ctypes.CDLL:
         L.conqur_init.argtypes = [ctypes.POINTER(Config), vp, ctypes.POINTER(vp)]
         L.conqur_step_batch.restype = i32
         L.conqur_step_batch.argtypes = [vp, vp, u64, u64]
+        L.conqur_step_batch_heads.restype = i32
+        L.conqur_step_batch_heads.argtypes = [vp, vp, u64, u64, ctypes.c_uint32, ctypes.c_uint32]
         L.conqur_get_batch_stats.restype = i32
         L.conqur_get_batch_stats.argtypes = [vp, vp]
         L.conqur_update_rotation.restype = i32
@@ -155,6 +157,14 @@ class Calibrator:
     def step_batch(self, X) -> None:
         p, T, stride = self._x(X)
         self._check(self._lib.conqur_step_batch(self._h, p, T, stride))
+
+    def step_batch_heads(self, X, head0: int, nheads: int) -> None:
+        """One batch for the heads [head0, head0 + nheads) only; X holds their nheads * dh columns."""
+        import torch
+        want = torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        if X.dim() != 2 or X.stride(1) != 1 or not X.is_cuda or X.dtype != want or X.shape[1] < nheads * self.dh:
+            raise ValueError(f"X must be a 2-D {want} device tensor with >= nheads * dh columns and unit column stride")
+        self._check(self._lib.conqur_step_batch_heads(self._h, X.data_ptr(), X.shape[0], X.stride(0), head0, nheads))
 
     def batch_stats(self) -> List[dict]:
         arr = (BatchStats * self.heads)()

@@ -54,6 +54,8 @@ struct conqur_ctx {
   float* M = nullptr;          // [heads][dh][dh]
   bool m_empty = true;         // M holds no rows: the next accumulate overwrites it
   bool have_rows = false;
+  // Heads of width 128 may be stepped in ranges (conqur_step_batch_heads): the same two facts per head.
+  std::vector<uint8_t> h_empty, h_rows;
   bf16_bits* Xt = nullptr;     // [np][d][pitch] scaled, transposed activations (fp16 plane, or 3 bf16 planes for fp32 input)
   bf16_bits* St = nullptr;     // [d][pitch] corner signs +-1, transposed (fp16, or bf16 for fp32 input)
   bf16_bits* Xs = nullptr;     // fp32 activations only: [3][tmax][d] split planes of X
@@ -242,6 +244,8 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   ctx->nonfinite = reinterpret_cast<int*>(ctx->fro2 + ctx->heads);
   A(dev_alloc(ctx, &ctx->dotrm_part, (size_t)ctx->heads * dot_rm_partials((int64_t)dh * dh)));
   ctx->l_base.assign(ctx->heads, 0.0);
+  ctx->h_empty.assign(ctx->heads, 1);
+  ctx->h_rows.assign(ctx->heads, 0);
   A(dev_alloc(ctx, reinterpret_cast<char**>(&ctx->Y), tmax * d * (ctx->f32 ? 4 : 2)));
   A(dev_alloc(ctx, &ctx->row_sse, 2 * tmax));   // per-row SSE, then per-row energy
   ctx->row_en = ctx->row_sse + tmax;
@@ -329,6 +333,58 @@ conqur_status conqur_get_clock_probe(conqur_ctx* ctx, float* out) {
   return CONQUR_OK;
 }
 
+// The fused per-head step (heads of width 128, bf16) on the heads [head0, head0 + nheads): X holds their nheads * 128
+// columns.  Every per-head buffer is addressed from head0; the token shares' partial M are packed for the range.
+static conqur_status step_fused(conqur_ctx* ctx, const void* X, int64_t T, int64_t stride, int head0, int nheads) {
+  hipStream_t s = ctx->stream;
+  const int64_t blk = (int64_t)ctx->dh * ctx->dh;
+  // as many token shares as fill the chip, within the room the partial sums were given at init
+  const int room = (int)((int64_t)ctx->head_splits * ctx->heads / nheads);
+  const int nsplit = std::min(room, head_step_splits(nheads, T));
+  const bool full = nheads == ctx->heads;
+  {
+    StageTimer tm(ctx, ST_ROTATE);   // the fused kernel: rotate + normalise + corner + accumulate
+    HIP_TRY(launch_head_step128(reinterpret_cast<const bf16_bits*>(X), T, stride, nheads, ctx->RopT + head0 * blk, ctx->Mpart, nsplit,
+                                ctx->nrm + (int64_t)head0 * ctx->tmax, ctx->tmax, ctx->L + head0, ctx->rows + head0,
+                                ctx->skipped + head0, ctx->nonfinite,
+                                ctx->taps ? ctx->St + (int64_t)head0 * ctx->dh * ctx->pitch : nullptr, ctx->pitch, s));
+  }
+  // M of the range: overwritten if none of its heads holds rows, added to if all do; a mixed range is cleared where empty
+  int n_empty = 0;
+  for (int h = head0; h < head0 + nheads; ++h) n_empty += ctx->h_empty[h];
+  if (n_empty != 0 && n_empty != nheads)
+    for (int h = head0; h < head0 + nheads; ++h)
+      if (ctx->h_empty[h]) HIP_TRY(launch_fill_zero(ctx->M + h * blk, blk * sizeof(float), s));
+  {
+    StageTimer tm(ctx, ST_ACCUM);    // the token shares' partial M, summed in a fixed order
+    HIP_TRY(launch_head_reduce(ctx->Mpart, nsplit, nheads, ctx->M + head0 * blk, n_empty == nheads ? 0 : 1, s));
+  }
+  for (int h = head0; h < head0 + nheads; ++h) { ctx->h_empty[h] = 0; ctx->h_rows[h] = 1; }
+  ctx->clk_wg[0] = ctx->clk_wg[1] = 0;
+  ctx->last_signs_valid = ctx->taps && full;   // the corner tap returns whole rows of width d
+  ctx->m_empty = false;
+  ctx->have_rows = true;
+  ctx->last_T = full ? T : 0;
+  return CONQUR_OK;
+}
+
+conqur_status conqur_step_batch_heads(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, uint32_t head0,
+                                      uint32_t nheads) {
+  if (!ctx) return CONQUR_EINVAL;
+  if (nheads < 1 || (uint64_t)head0 + nheads > (uint64_t)ctx->heads) return fail(ctx, CONQUR_EINVAL, "head range outside [0, heads)");
+  if (head0 == 0 && nheads == (uint32_t)ctx->heads) return conqur_step_batch(ctx, X, T64, stride64);
+  if (!ctx->head_fused)
+    return fail(ctx, CONQUR_EINVAL, "a partial head range needs heads of width 128 and bf16 activations");
+  if (!X) return fail(ctx, CONQUR_EINVAL, "X_dev is NULL");
+  if (T64 < 1 || (int64_t)T64 > ctx->tmax) return fail(ctx, CONQUR_EINVAL, "T must be in [1, max_tokens]");
+  if (stride64 < (uint64_t)nheads * ctx->dh) return fail(ctx, CONQUR_EINVAL, "row_stride_elems < nheads * dh");
+  if ((reinterpret_cast<uintptr_t>(X) & 15) || ((stride64 * 2) & 15))
+    return fail(ctx, CONQUR_EINVAL, "X_dev base and row pitch must be 16-byte aligned");
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  StageTimer whole(ctx, ST_STEP, 1);
+  return step_fused(ctx, X, (int64_t)T64, (int64_t)stride64, (int)head0, (int)nheads);
+}
+
 conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64) {
   conqur_status st = check_x(ctx, X, T64, stride64);
   if (st != CONQUR_OK) return st;
@@ -337,25 +393,7 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
   const int64_t Tk = round_up(T, 64);
   hipStream_t s = ctx->stream;
   StageTimer whole(ctx, ST_STEP, 1);   // ends when the function returns
-  if (ctx->head_fused) {
-    const int nsplit = std::min(ctx->head_splits, head_step_splits(ctx->heads, T));
-    {
-      StageTimer tm(ctx, ST_ROTATE);   // the fused kernel: rotate + normalise + corner + accumulate
-      HIP_TRY(launch_head_step128(reinterpret_cast<const bf16_bits*>(X), T, stride, ctx->heads, ctx->RopT, ctx->Mpart, nsplit,
-                                  ctx->nrm, ctx->tmax, ctx->L, ctx->rows, ctx->skipped, ctx->nonfinite,
-                                  ctx->taps ? ctx->St : nullptr, ctx->pitch, s));
-    }
-    {
-      StageTimer tm(ctx, ST_ACCUM);    // the token shares' partial M, summed in a fixed order
-      HIP_TRY(launch_head_reduce(ctx->Mpart, nsplit, ctx->heads, ctx->M, ctx->m_empty ? 0 : 1, s));
-    }
-    ctx->clk_wg[0] = ctx->clk_wg[1] = 0;
-    ctx->last_signs_valid = ctx->taps;
-    ctx->m_empty = false;
-    ctx->have_rows = true;
-    ctx->last_T = T;
-    return CONQUR_OK;
-  }
+  if (ctx->head_fused) return step_fused(ctx, X, T, stride, 0, ctx->heads);
   ctx->last_signs_valid = true;
   {
     StageTimer tm(ctx, ST_PREP);
@@ -468,6 +506,9 @@ static double step_cubic(double l, double u, double* a, double* b) {
 conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) {
   if (!ctx) return CONQUR_EINVAL;
   if (!ctx->have_rows) return fail(ctx, CONQUR_ESTATE, "update_rotation: no rows accumulated since the last update");
+  for (int q = 0; q < ctx->heads; ++q)
+    if (ctx->head_fused && !ctx->h_rows[q])
+      return fail(ctx, CONQUR_ESTATE, "update_rotation: a head range has no rows since the last update");
   HIP_TRY(hipSetDevice(ctx->cfg.device));
   hipStream_t s = ctx->stream;
   const int h = ctx->heads, dh = ctx->dh;
@@ -759,6 +800,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   std::memcpy(&nonfinite, resblk + 3 * h, sizeof(int));
   ctx->m_empty = true;
   ctx->have_rows = false;
+  ctx->h_empty.assign(h, 1);
+  ctx->h_rows.assign(h, 0);
   if (out) {
     float ms = 0.0f;
     HIP_TRY(hipEventElapsedTime(&ms, ctx->ev[ST_UPDATE][0], ctx->ev[ST_UPDATE][1]));
@@ -913,6 +956,10 @@ conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, ui
   std::vector<unsigned long long> rows(ctx->heads);
   if (n_rows) HIP_TRY(hipMemcpyAsync(rows.data(), ctx->rows, ctx->heads * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  if (M_host && !ctx->m_empty)   // heads stepped in ranges: those without rows still hold the M of before the last update
+    for (int i = 0; i < ctx->heads; ++i)
+      if (ctx->h_empty[i] && ctx->head_fused)
+        std::memset(M_host + (size_t)i * ctx->dh * ctx->dh, 0, (size_t)ctx->dh * ctx->dh * sizeof(float));
   if (n_rows) for (int i = 0; i < ctx->heads; ++i) n_rows[i] = rows[i];
   return CONQUR_OK;
 }
@@ -946,6 +993,8 @@ conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float
     HIP_TRY(hipMemcpyAsync(ctx->M, M_host, blk * sizeof(float), hipMemcpyHostToDevice, s));
     ctx->m_empty = false;
     ctx->have_rows = true;
+    ctx->h_empty.assign(h, 0);
+    ctx->h_rows.assign(h, 1);
     ctx->l_base.assign(h, 0.0);   // the rows behind the old M are gone
   }
   HIP_TRY(hipStreamSynchronize(s));

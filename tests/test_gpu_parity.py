@@ -327,6 +327,98 @@ def test_free_running_streams(B):
             cal.close()
 
 
+def test_head_ranges_carry_several_layers(B):
+    """One context with the per-head rotations of two layers (2 x 16 heads of width 128): every layer's batches go to
+    its own head range, in any order and with different token counts per call; M, the statistics and the batched
+    update agree with the oracle stepping the concatenated rows."""
+    import torch
+    w = I.small_workload(4096, 384, n_batches=2, heads=32, seed=131, prox_lambda=0.0)
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(w.d, w.heads, w.dtype, R0, 0.0)
+    cal = B.Calibrator(w.d, w.heads, w.dtype, R0, max_tokens=384)
+    half = w.d // 2
+    try:
+        with pytest.raises(B.ConqurError) as e:
+            cal.update_rotation()
+        assert e.value.status == B.ESTATE
+        X0, X1 = I.batch(w, 0, 384), I.batch(w, 1, 200)
+        # layer B first, then layer A twice, then layer B again: ranges empty / filled in mixed order
+        cal.step_batch_heads(B.to_device(np.ascontiguousarray(X0[:, half:]), w.dtype), 16, 16)
+        with pytest.raises(B.ConqurError) as e:          # heads 0..15 have no rows yet
+            cal.update_rotation()
+        assert e.value.status == B.ESTATE
+        cal.step_batch_heads(B.to_device(np.ascontiguousarray(X0[:, :half]), w.dtype), 0, 16)
+        cal.step_batch_heads(B.to_device(np.ascontiguousarray(X1[:, :half]), w.dtype), 0, 16)
+        # a range across both layers with one of its heads' M cleared on the host side of the bookkeeping
+        Xd1 = B.to_device(X1, w.dtype)
+        cal.step_batch_heads(Xd1[:, half:], 16, 16)      # a view: row stride d, columns of the upper half
+        oc.step_batch(X0)
+        oc.step_batch(X1)
+        _, Mg, _ = cal.get_state(want_R=False)
+        st = cal.batch_stats()
+        for h in range(w.heads):
+            relM = np.linalg.norm(Mg[h] - oc.M[h]) / np.linalg.norm(oc.M[h])
+            assert relM <= TOL_M, (h, relM)
+            assert st[h]["rows"] == oc.n[h] and st[h]["skipped"] == oc.skipped[h]
+            assert abs(st[h]["l1"] - oc.L[h]) <= TOL_REL * abs(oc.L[h])
+        with pytest.raises(B.ConqurError) as e:          # the corner tap has whole rows only
+            cal.last_corners(200)
+        assert e.value.status == B.ESTATE
+        compare_update(B, cal, oc, w, "two layers, one update", check_R=False)
+        _, M, n = cal.get_state(want_R=False)
+        assert not M.any() and not n.any()
+        # next round: only one layer stepped -> its heads have M, the others read as empty
+        cal.step_batch_heads(B.to_device(np.ascontiguousarray(X0[:, :half]), w.dtype), 0, 16)
+        _, M, _ = cal.get_state(want_R=False)
+        assert M[:16].any() and not M[16:].any()
+        with pytest.raises(B.ConqurError) as e:
+            cal.step_batch_heads(Xd1, 20, 16)            # range past the last head
+        assert e.value.status == B.EINVAL
+    finally:
+        cal.close()
+    # a context of another kind refuses partial ranges
+    g = B.Calibrator(256, 4, "bf16", np.stack([np.eye(64, dtype=np.float32)] * 4), max_tokens=64)
+    try:
+        with pytest.raises(B.ConqurError) as e:
+            g.step_batch_heads(torch.zeros(8, 128, dtype=torch.bfloat16, device="cuda:0"), 0, 2)
+        assert e.value.status == B.EINVAL
+    finally:
+        g.close()
+
+
+def test_batched_update_of_many_layers_fills_the_device(B):
+    """8 layers x 32 heads of width 128 in one context: one batched update against 8 single-layer updates (timing only
+    printed; the results of a layer do not depend on what else is in the batch)."""
+    w1 = I.WORKLOADS["c4"]
+    L = 8
+    R1 = I.initial_rotation(w1)
+    X = I.batch(w1, 0, 512)
+    Xd = B.to_device(X, "bf16")
+    one = B.Calibrator(w1.d, w1.heads, "bf16", R1, max_tokens=512)
+    big = B.Calibrator(L * w1.d, L * w1.heads, "bf16", np.concatenate([R1] * L), max_tokens=512)
+    try:
+        t_one = []
+        for rep in range(3):
+            one.step_batch(Xd)
+            _, st = one.update_rotation()
+            t_one.append(st[0]["ms"])
+        R_one, _, _ = one.get_state(want_M=False)
+        t_big = []
+        for rep in range(3):
+            for l in range(L):
+                big.step_batch_heads(Xd, l * w1.heads, w1.heads)
+            _, st = big.update_rotation()
+            t_big.append(st[0]["ms"])
+        R_big, _, _ = big.get_state(want_M=False)
+        say(f"  update of 32 heads: {min(t_one):.3f} ms; batched update of {L} x 32 heads: {min(t_big):.3f} ms "
+            f"({L * min(t_one) / min(t_big):.1f}x the throughput)")
+        for l in range(L):      # every layer saw the same batches as the single-layer context
+            assert np.array_equal(R_big[l * w1.heads:(l + 1) * w1.heads], R_one)
+    finally:
+        one.close()
+        big.close()
+
+
 def test_pooled_batches_before_one_update(B):
     """Alg. 1 pools several sites into one update: three step_batch calls (shrinking T), one update."""
     w = I.small_workload(256, 384, n_batches=3, seed=77, prox_lambda=0.0)
