@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--steps", type=int, default=16)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="tokens per batch instead of the workload's own (exploration only: the line's config then says so)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = one whole batch")
     ap.add_argument("--pmc-copy", action="store_true",
@@ -86,10 +88,10 @@ def main():
         print("bench.py: no HIP device", file=sys.stderr)
         sys.exit(1)
     w = I.WORKLOADS[args.workload]
-    T, d = w.tokens_per_batch, w.d
+    T, d = args.tokens or w.tokens_per_batch, w.d
     K, W = args.steps, args.warmup
     n_distinct = min(K + W, 8)
-    host = [I.batch(w, b) for b in range(n_distinct)]
+    host = [I.batch(w, b, T) for b in range(n_distinct)]
     R0 = I.initial_rotation(w)
     dev = [B.to_device(x, w.dtype) for x in host]
     cal = B.Calibrator(d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
@@ -185,7 +187,7 @@ def main():
             "bound": "mfma", "kernel": "gemm_nt_kernel (rotate+corner launch and accumulate launch of step_batch)",
             "achieved": step_flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": step_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if T == w.tokens_per_batch else None,
             "flops_per_launch_pair": step_flops, "ms_per_launch_pair": gemm_ms,
             "measured_over": "per-kernel HIP events on the library's stream, second pass of the same steps",
             # in-kernel probe: the shader clock the chip sustains while these kernels' MFMAs run (the published peak
