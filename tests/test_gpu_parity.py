@@ -197,6 +197,8 @@ def test_c1_stream_fp32(B):
     (192, 500, 4, "bf16", 0.0),      # per-head blocks of width 48
     (128, 257, 1, "f32", 0.0),       # fp32 activations, odd token count
     (64, 1, 1, "bf16", 0.5),         # a single token
+    (1024, 300, 2, "bf16", 0.1),     # two heads of width 512: batched GEMMs whose symmetric products run on the
+                                     # tiles on and above the diagonal (8 tiles of 64 per side)
 ])
 def test_small_streams(B, d, T, heads, dtype, lam):
     w = I.small_workload(d, T, n_batches=2, heads=heads, dtype=dtype, seed=100 + d + T, prox_lambda=lam,
