@@ -157,6 +157,20 @@ def test_c5_sampled(B):
             assert relM <= 1e-3
         finally:
             cal2.close()
+        # the scores and the emitted fake-quantised rows on the whole batch, against the oracle on the sampled rows
+        Xs = np.ascontiguousarray(X[rows])
+        Qg = cal.rotate_quant(Xd, 4, True, 0.9).float().cpu().numpy()[rows]
+        Qo = oc.fake_quant(Xs, 4, True, 0.9)
+        Yo = oc.rotate(Xs)
+        stepw = (0.9 * (Yo.max(1) - Yo.min(1)) / 15)[:, None]
+        diff = np.abs(Qg - Qo)
+        assert np.all(diff <= stepw * (1 + 2.0 ** -6) + 2.0 ** -7 * np.abs(Qo))
+        near = diff <= 2.0 ** -6 * (np.abs(Qo) + stepw)
+        say(f"  c5: fake-quant rows (sample): {100 * (1 - near.mean()):.4f} % of the entries on a neighbouring level")
+        assert near.mean() >= 0.997
+        pr_g, rho_g = cal.row_diagnostics(Xd)
+        pr_o, rho_o = oc.row_diagnostics(Xs)
+        assert np.allclose(pr_g[rows], pr_o, rtol=1e-3, atol=1e-7) and np.allclose(rho_g[rows], rho_o, rtol=1e-3, atol=1e-7)
         # update at d = 8192 from the GPU's M, checked by properties
         _, ust = cal.update_rotation()
         R, _, _ = cal.get_state(want_M=False)
