@@ -248,9 +248,13 @@ __global__ void __launch_bounds__(256) k_head_reduce(const float* __restrict__ M
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= n_total) return;
   float4 acc = accumulate ? *reinterpret_cast<const float4*>(M + i) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  for (int s = 0; s < nsplit; ++s) {
-    const float4 v = *reinterpret_cast<const float4*>(Mpart + s * n_total + i);
-    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  for (int s0 = 0; s0 < nsplit; s0 += 8) {   // eight shares' loads in flight, added in share order
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = s0 + u < nsplit ? *reinterpret_cast<const float4*>(Mpart + (s0 + u) * n_total + i) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
   }
   *reinterpret_cast<float4*>(M + i) = acc;
 }
