@@ -235,6 +235,29 @@ conqur_status conqur_set_taps(conqur_ctx* ctx, int enable);
  */
 conqur_status conqur_get_last_corners(conqur_ctx* ctx, int8_t* signs_host, float* norms_host);
 
+/*
+ * For callers that cannot allocate device memory or wait for the stream (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the score of
+ * conqur_quant_error (zero_point = 0; clip_ratio ignored) or conqur_quant_error_zp (zero_point
+ * = 1) on rows that are ALREADY rotated -- Y_dev is what conqur_rotate wrote -- with the two
+ * results left in device memory.  No context: the per-row results the score kernels exchange
+ * live in a static device array of the library (2 floats per row, 512 KiB, held by every GPU
+ * the library has run on until the process ends), so the call allocates nothing, copies
+ * nothing to the host and returns without waiting.  Runs on the CURRENT device; `stream` must
+ * belong to it (NULL = its default stream).  The array's address is looked up once per device,
+ * by conqur_init or by the first call on that device: make that first call outside any graph
+ * capture.  Y_dev: DEVICE, T rows of row_stride_elems >= d elements of dtype (conqur_dtype),
+ * 16-byte aligned base and row pitch; 1 <= T <= 65536 rows per call (more: CONQUR_EINVAL, split
+ * the rows over several calls and add the results); d a multiple of 16, at most 65536.
+ * out_dev: DEVICE, 2 doubles, overwritten with { sum (y - q)^2, sum y^2 } once the stream has
+ * passed the call's kernels.  All calls on one GPU share the array, which keeps the last
+ * call's per-row values: calls that overlap in time on one GPU (different streams) race; calls
+ * on one stream are ordered and safe.  Errors: CONQUR_EINVAL (arguments as above, bits outside
+ * [2, 8], zero_point > 1, clip_ratio outside (0, 1]), CONQUR_EHIP.
+ */
+conqur_status conqur_score_rows_static(const void* Y_dev, uint32_t dtype, uint64_t T, uint64_t d, uint64_t row_stride_elems,
+                                       uint32_t bits, uint32_t zero_point, float clip_ratio, double* out_dev, void* stream);
+
 /* Device times (ms) of the most recent call of each kind, measured with HIP events on the
  * context's stream.  level 0: off.  level 1: one event pair around each whole call (what a
  * caller's pipeline sees: the call's kernels run back to back).  level 2: additionally one

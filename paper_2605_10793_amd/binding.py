@@ -23,7 +23,7 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "conqur_init", "conqur_step_batch", "conqur_step_batch_heads", "conqur_get_batch_stats", "conqur_update_rotation",
     "conqur_quant_error", "conqur_quant_error_zp", "conqur_rotate", "conqur_rotate_quant", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
-    "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
+    "conqur_score_rows_static", "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
 
 
@@ -88,6 +88,8 @@ def load() -> ctypes.CDLL:
         L.conqur_set_state.argtypes = [vp, vp, vp]
         L.conqur_get_last_corners.restype = i32
         L.conqur_get_last_corners.argtypes = [vp, vp, vp]
+        L.conqur_score_rows_static.restype = i32
+        L.conqur_score_rows_static.argtypes = [vp, u32, u64, u64, u64, u32, u32, ctypes.c_float, vp, vp]
         L.conqur_set_taps.restype = i32
         L.conqur_set_taps.argtypes = [vp, i32]
         L.conqur_set_timing.restype = i32
@@ -265,6 +267,25 @@ class Calibrator:
         self._check(self._lib.conqur_get_clock_probe(self._h, _np_ptr(out)))
         keys = ["clock_mhz", "loop_us", "prologue_us", "epilogue_us"]
         return {g: {k: float(out[4 * j + i]) for i, k in enumerate(keys)} for j, g in enumerate(("rotate", "accumulate"))}
+
+
+def score_rows_static(Y, out, bits: int = 4, zero_point: bool = False, clip_ratio: float = 1.0, d: Optional[int] = None,
+                      stream: Optional[int] = None) -> None:
+    """conqur_score_rows_static on the rotated rows Y (2-D device tensor, bf16 or fp32): out (device tensor of 2 float64)
+    receives {SSE, energy} once the stream has passed the call; d: row width used (default: all columns of Y).
+    Allocates nothing and does not synchronise."""
+    import torch
+    if Y.dim() != 2 or Y.stride(1) != 1 or not Y.is_cuda or Y.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("Y must be a 2-D bf16 or fp32 device tensor with unit column stride")
+    if out.dtype != torch.float64 or out.numel() < 2 or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out must be a contiguous device tensor of 2 float64")
+    if stream is None:
+        stream = torch.cuda.current_stream(Y.device).cuda_stream
+    st = load().conqur_score_rows_static(Y.data_ptr(), BF16 if Y.dtype == torch.bfloat16 else F32, Y.shape[0], Y.shape[1] if d is None else d,
+                                         Y.stride(0), bits, 1 if zero_point else 0, ctypes.c_float(clip_ratio),
+                                         out.data_ptr(), ctypes.c_void_p(stream))
+    if st != OK:
+        raise ConqurError(st, "conqur_score_rows_static failed")
 
 
 def to_device(x: np.ndarray, dtype: str, device: str = "cuda:0"):

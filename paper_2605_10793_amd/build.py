@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libconqur.so")
-SOURCES = ["gemm_nt.hip", "kernels.hip", "head_step.hip", "head_polar.hip", "conqur.hip"]
+SOURCES = ["gemm_nt.hip", "kernels.hip", "head_step.hip", "head_polar.hip", "static_score.hip", "conqur.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          # fp32/fp64 atomicAdd as the hardware's L2 atomics (device memory is coarse grained);
          # the default lowers them to compare-and-swap loops, which crawl under contention

@@ -204,6 +204,10 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return CONQUR_EHIP;
   if (hipSetDevice(cfg->device) != hipSuccess) return CONQUR_EHIP;
+  {   // conqur_score_rows_static's array on this device: its address is looked up here, outside any graph capture
+    float* scratch = nullptr;
+    if (static_scratch_for_current_device(&scratch) != hipSuccess) return CONQUR_EHIP;
+  }
 
   conqur_ctx* ctx = new (std::nothrow) conqur_ctx();
   if (!ctx) return CONQUR_ENOMEM;

@@ -95,4 +95,8 @@ hipError_t launch_sum_partials(const double* part, int n, int heads, double* out
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
+// Device address, on the current device, of the static array conqur_score_rows_static keeps its per-row results in
+// (static_score.hip); looked up once per device.
+hipError_t static_scratch_for_current_device(float** out);
+
 }  // namespace conqur
