@@ -49,16 +49,22 @@ typedef struct {
   uint32_t d;               /* row width of X; d % heads == 0, (d/heads) % 16 == 0, d/heads <= 8192 */
   uint32_t heads;           /* 1 = one d x d rotation; h > 1 = h independent (d/h) x (d/h) problems */
   uint32_t act_dtype;       /* conqur_dtype of X; the rotate operand is R rounded to this type      */
-  uint32_t max_tokens;      /* largest T passed to step_batch / quant_error (sizes the workspaces)  */
-  float prox_lambda;        /* 0: R <- polar(M), the paper's update (Sec. 3.3).  > 0: R <- polar(M +
-                               lambda * tau * R_prev), tau = ||M||_F / sqrt(dh): the proximal reading
-                               that makes the update unique when M is rank deficient               */
+  uint32_t max_tokens;      /* largest T passed to step_batch / quant_error (sizes the workspaces);
+                               (d/heads) * round_up(max_tokens, 64) < 2^30                           */
+  float prox_lambda;        /* R <- polar(M + lambda * tau * R_prev), tau = ||M||_F / sqrt(dh): the proximal
+                               reading that makes the update unique when M is rank deficient.  0 asks for
+                               the paper's update R <- polar(M) (Sec. 3.3) and is taken as the limit
+                               lambda -> 0+ at fp32 resolution: values below 2^-20 are raised to 2^-20
+                               (that ties R to R_prev on the null space of M, where every completion is
+                               optimal, and breaks exact degeneracies a polynomial iteration would keep;
+                               it moves <R, M> by less than 1e-6 relative)                            */
   float polar_tol;          /* stop when ||X^T X - I||_F <= tol; 0 selects 8e-5                      */
   uint32_t polar_max_iters; /* 0 selects 200                                                        */
-  uint32_t polar_precision; /* arithmetic of the main polar iterations: 0 = single bf16 operands (fast;
-                               meets the orthogonality and objective tolerances, R itself deviates on
-                               directions with small singular values), 1 = two bf16 planes per operand
-                               (about 16 significant bits), 2 = three planes (fp32-equivalent products).
+  uint32_t polar_precision; /* arithmetic of the main polar iterations: 0 = single fp16 operands (fast; 11
+                               significant bits: meets the orthogonality and objective tolerances, R itself
+                               deviates a little on directions with small singular values, where a step's
+                               rounding is amplified by 1/sigma), 1 = two bf16 planes per operand (about 16
+                               significant bits), 2 = three planes (fp32-equivalent products).
                                The closing iterations always run fp32-equivalent.                     */
   uint32_t polar_verify;    /* orthogonality of the final iterate: 0 = bounded from the last measured
                                residual (exact-arithmetic residual of the closing step, from ||D^3||_F,
@@ -72,8 +78,9 @@ typedef struct {
 typedef struct {
   uint64_t rows;    /* rows that entered M                                                         */
   uint64_t skipped; /* rows skipped: all-zero or non-finite head slice                             */
-  double l1;        /* L = sum_i ||y_i||_1 / ||x_i||_2 ; Eq. 1 equals 2*rows - 2*L/sqrt(dh)
-                       (the l1 identity of Sec. 3.2)                                               */
+  double l1;        /* L = sum_i ||y_i||_1 / ||x_i||_2                                               */
+  double objective; /* Eq. 1 summed over those rows, sum_i || y_i/||x_i|| - c_i ||^2, evaluated through
+                       the l1 identity of Sec. 3.2 as 2*rows - 2*L/sqrt(dh)                          */
 } conqur_batch_stats;
 
 /* Per-head result of one Procrustes update (HOST struct). */
@@ -104,8 +111,8 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
  * the rotated row (Eq. 2), and add (x_i/||x_i||)^T c_i to M.  May be called many
  * times before one update (Alg. 1 pools all sites of a mini-batch).
  * X_dev: DEVICE, T rows of row_stride_elems elements of act_dtype, of which the
- * first d are used; 16-byte aligned base and row pitch.  1 <= T <= max_tokens.
- * The caller keeps ownership of X and may reuse it once the stream has passed
+ * first d are used; 16-byte aligned base and row pitch.  1 <= T <= max_tokens,
+ * T * row_stride_elems < 2^30 (CONQUR_EINVAL otherwise).  The caller keeps ownership of X and may reuse it once the stream has passed
  * this call's kernels.  Asynchronous; never touches the host.
  */
 conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems);
@@ -210,9 +217,11 @@ conqur_status conqur_row_diagnostics(conqur_ctx* ctx, const void* X_dev, uint64_
 /*
  * Copy state to the host / replace it (checkpointing, and teacher-forced parity
  * tests).  R_host, M_host: HOST, heads*dh*dh floats or NULL.  n_rows_host: HOST,
- * `heads` entries or NULL.  set_state(R) also refreshes the rotate operand;
- * set_state(M) marks the statistics as holding rows (row count unknown -> 1).
- * Both synchronise the stream.
+ * `heads` entries or NULL: the rows that entered M since the last update (as
+ * conqur_batch_stats.rows).  set_state(R) also refreshes the rotate operand;
+ * set_state(M) marks the statistics as holding rows, so that an update may follow; the
+ * row and skipped counters and the l1 term then still describe the rows stepped through
+ * the library, not the M that was written.  Both synchronise the stream.
  */
 conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, uint64_t* n_rows_host);
 conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float* M_host);
@@ -279,6 +288,10 @@ conqur_status conqur_get_timing(conqur_ctx* ctx, float* out_host);
  * [2] its prologue (first operand tiles arriving) (us)      [3] its epilogue (us)
  * [4..7] the same for the accumulate GEMM.  Zeros if no probe was taken.  Synchronises.           */
 conqur_status conqur_get_clock_probe(conqur_ctx* ctx, float* out_host);
+
+/* Environment: CONQUR_TRACE (set to anything) makes conqur_update_rotation print one line per polar step to stderr
+ * (interval, coefficients, measured and predicted residuals) and measure a few quantities it otherwise skips; results
+ * are unchanged.  Nothing else is read from the environment. */
 
 /* Last error text of this context (HOST string owned by the context; "" if none). */
 const char* conqur_last_error(const conqur_ctx* ctx);

@@ -35,7 +35,8 @@ class Config(ctypes.Structure):
 
 
 class BatchStats(ctypes.Structure):
-    _fields_ = [("rows", ctypes.c_uint64), ("skipped", ctypes.c_uint64), ("l1", ctypes.c_double)]
+    _fields_ = [("rows", ctypes.c_uint64), ("skipped", ctypes.c_uint64), ("l1", ctypes.c_double),
+                ("objective", ctypes.c_double)]
 
 
 class UpdateStats(ctypes.Structure):
@@ -171,12 +172,11 @@ class Calibrator:
     def batch_stats(self) -> List[dict]:
         arr = (BatchStats * self.heads)()
         self._check(self._lib.conqur_get_batch_stats(self._h, arr))
-        return [dict(rows=int(a.rows), skipped=int(a.skipped), l1=float(a.l1)) for a in arr]
+        return [dict(rows=int(a.rows), skipped=int(a.skipped), l1=float(a.l1), objective=float(a.objective)) for a in arr]
 
     def objective(self) -> np.ndarray:
-        """Eq. 1 through the l1 identity (Sec. 3.2): 2*rows - 2*L/sqrt(dh), per head."""
-        s = self.batch_stats()
-        return np.array([2.0 * a["rows"] - 2.0 * a["l1"] / np.sqrt(float(self.dh)) for a in s])
+        """Eq. 1 of the rows accumulated since the last update, per head (conqur_batch_stats.objective)."""
+        return np.array([a["objective"] for a in self.batch_stats()])
 
     def update_rotation(self, allow: Tuple[int, ...] = ()) -> Tuple[int, List[dict]]:
         arr = (UpdateStats * self.heads)()

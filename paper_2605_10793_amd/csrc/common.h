@@ -48,6 +48,12 @@ __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
   const f32x2 v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// Two values as fp16 (round to nearest even), packed lo | hi << 16.
+__device__ __forceinline__ uint32_t f32x2_to_f16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
 __device__ __forceinline__ bf16_bits f32_to_f16(float f) {
   const _Float16 h = (_Float16)f;  // round to nearest even
   return __builtin_bit_cast(unsigned short, h);
@@ -71,5 +77,11 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// The accumulate operand holds the unit rows x^ = x / ||x|| times this power of two, in fp16.  |x^| <= 1, and on
+// outlier-dominated rows most entries are 1e-3 .. 1e-5: times 1/sqrt(dh) (the corner's magnitude) they would sit in
+// fp16's subnormal range (below 6.1e-5) and lose bits; scaled up they keep all 11.  The factor and 1/sqrt(dh) are
+// applied to the fp32 result instead (exact power of two; the sum cannot overflow: 64 * tokens * 1).
+constexpr float kXhatScale = 64.0f;
 
 }  // namespace conqur

@@ -86,6 +86,9 @@ struct conqur_ctx {
   bool head_fused = false;
   float* Mpart = nullptr;                            // [head_splits][heads][128][128] partial M of the token shares
   int head_splits = 0;
+  int parts_pending = 0;                             // > 0: M of all heads still lies in that many token shares of Mpart
+                                                     // (a first batch's shares are summed when M is next needed: by the
+                                                     // update, which takes ||M||_F from the same pass, or by a reader)
   bool taps = false;                                 // keep the corner signs of every step for conqur_get_last_corners
   bool last_signs_valid = false;
 
@@ -143,6 +146,7 @@ conqur_status check_x(conqur_ctx* ctx, const void* X, uint64_t T, uint64_t strid
   const uint64_t esz = ctx->f32 ? 4 : 2;
   if ((reinterpret_cast<uintptr_t>(X) & 15) || ((stride * esz) & 15))
     return fail(ctx, CONQUR_EINVAL, "X_dev base and row pitch must be 16-byte aligned");
+  if (T * stride >= (1ull << 30)) return fail(ctx, CONQUR_EINVAL, "T * row_stride_elems must be below 2^30");
   return CONQUR_OK;
 }
 
@@ -201,6 +205,9 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   if (cfg->act_dtype != CONQUR_F32 && cfg->act_dtype != CONQUR_BF16) return CONQUR_EINVAL;
   if (cfg->max_tokens == 0 || cfg->max_tokens > (1u << 22) || cfg->polar_precision > 2 || cfg->polar_verify > 1) return CONQUR_EINVAL;
   if (!(cfg->prox_lambda >= 0.0f) || !(cfg->polar_tol >= 0.0f)) return CONQUR_EINVAL;
+  // the GEMM kernels address an operand's rows through 32-bit byte offsets: the transposed operands [dh][pitch]
+  if ((int64_t)dh * round_up((int64_t)cfg->max_tokens, 64) >= (1ll << 30)) return CONQUR_EINVAL;
+  if (cfg->act_dtype == CONQUR_F32 && (int64_t)cfg->d * cfg->max_tokens >= (1ll << 30)) return CONQUR_EINVAL;   // split planes of X
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return CONQUR_EHIP;
   if (hipSetDevice(cfg->device) != hipSuccess) return CONQUR_EHIP;
@@ -337,6 +344,14 @@ conqur_status conqur_get_clock_probe(conqur_ctx* ctx, float* out) {
   return CONQUR_OK;
 }
 
+// Sum the pending token shares of a first batch into M (see conqur_ctx::parts_pending).
+static conqur_status materialise_m(conqur_ctx* ctx) {
+  if (!ctx->parts_pending) return CONQUR_OK;
+  HIP_TRY(launch_head_reduce(ctx->Mpart, ctx->parts_pending, ctx->heads, ctx->M, 0, nullptr, ctx->stream));
+  ctx->parts_pending = 0;
+  return CONQUR_OK;
+}
+
 // The fused per-head step (heads of width 128, bf16) on the heads [head0, head0 + nheads): X holds their nheads * 128
 // columns.  Every per-head buffer is addressed from head0; the token shares' partial M are packed for the range.
 static conqur_status step_fused(conqur_ctx* ctx, const void* X, int64_t T, int64_t stride, int head0, int nheads) {
@@ -346,6 +361,10 @@ static conqur_status step_fused(conqur_ctx* ctx, const void* X, int64_t T, int64
   const int room = (int)((int64_t)ctx->head_splits * ctx->heads / nheads);
   const int nsplit = std::min(room, head_step_splits(nheads, T));
   const bool full = nheads == ctx->heads;
+  if (ctx->parts_pending) {   // the previous batch's shares still stand for M: sum them before Mpart is written again
+    conqur_status st = materialise_m(ctx);
+    if (st != CONQUR_OK) return st;
+  }
   {
     StageTimer tm(ctx, ST_ROTATE);   // the fused kernel: rotate + normalise + corner + accumulate
     HIP_TRY(launch_head_step128(reinterpret_cast<const bf16_bits*>(X), T, stride, nheads, ctx->RopT + head0 * blk, ctx->Mpart, nsplit,
@@ -359,9 +378,15 @@ static conqur_status step_fused(conqur_ctx* ctx, const void* X, int64_t T, int64
   if (n_empty != 0 && n_empty != nheads)
     for (int h = head0; h < head0 + nheads; ++h)
       if (ctx->h_empty[h]) HIP_TRY(launch_fill_zero(ctx->M + h * blk, blk * sizeof(float), s));
-  {
+  if (full && n_empty == nheads) {
+    // First batch since the update, all heads: the shares are left where they are.  Whoever needs M next sums them --
+    // normally the update, in the pass that also yields ||M||_F -- so a step that is followed by its update (Alg. 1)
+    // costs one launch and one round trip of M less.
+    ctx->parts_pending = nsplit;
+    ctx->ev_valid[ST_ACCUM] = false;
+  } else {
     StageTimer tm(ctx, ST_ACCUM);    // the token shares' partial M, summed in a fixed order
-    HIP_TRY(launch_head_reduce(ctx->Mpart, nsplit, nheads, ctx->M + head0 * blk, n_empty == nheads ? 0 : 1, s));
+    HIP_TRY(launch_head_reduce(ctx->Mpart, nsplit, nheads, ctx->M + head0 * blk, n_empty == nheads ? 0 : 1, nullptr, s));
   }
   for (int h = head0; h < head0 + nheads; ++h) { ctx->h_empty[h] = 0; ctx->h_rows[h] = 1; }
   ctx->clk_wg[0] = ctx->clk_wg[1] = 0;
@@ -431,6 +456,7 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
     for (int q = 0; q < sl.n; ++q) { g.a_seg[q] = sl.a[q] * (int64_t)ctx->d * ctx->pitch; g.b_seg[q] = 0; }
     g.C = ctx->M; g.ldc = ctx->dh; g.batchC = (int64_t)ctx->dh * ctx->dh;
     g.accumulate = ctx->m_empty ? 0 : 1;
+    g.out_scale = 1.0f / (kXhatScale * std::sqrt((float)ctx->dh));   // the operand carries kXhatScale x^, the corner 1/sqrt(dh)
     g.ab_f16 = ctx->f32 ? 0 : 1;
     const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
     ctx->clk_wg[1] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
@@ -479,7 +505,10 @@ conqur_status conqur_get_batch_stats(conqur_ctx* ctx, conqur_batch_stats* out) {
   std::vector<unsigned long long> rows, skipped;
   const conqur_status st = read_stats(ctx, &L, &rows, &skipped);
   if (st != CONQUR_OK) return st;
-  for (int i = 0; i < ctx->heads; ++i) { out[i].rows = rows[i]; out[i].skipped = skipped[i]; out[i].l1 = L[i]; }
+  for (int i = 0; i < ctx->heads; ++i) {
+    out[i].rows = rows[i]; out[i].skipped = skipped[i]; out[i].l1 = L[i];
+    out[i].objective = 2.0 * (double)rows[i] - 2.0 * L[i] / std::sqrt((double)ctx->dh);   // the l1 identity of Sec. 3.2
+  }
   return CONQUR_OK;
 }
 
@@ -521,9 +550,20 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   const bool trace = std::getenv("CONQUR_TRACE") != nullptr;
   if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][0], s));
 
-  HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->dotrm_part, ctx->fro2, s));
+  if (ctx->parts_pending) {   // per-head step: M is summed from the token shares here, ||M||_F^2 from the same pass
+    HIP_TRY(launch_head_reduce(ctx->Mpart, ctx->parts_pending, h, ctx->M, 0, ctx->dotrm_part, s));
+    HIP_TRY(launch_sum_partials(ctx->dotrm_part, kHeadReduceParts, h, ctx->fro2, s));
+    ctx->parts_pending = 0;
+  } else {
+    HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->dotrm_part, ctx->fro2, s));
+  }
 
   const int np_main = 1 + (int)ctx->cfg.polar_precision;
+  // Single-plane main steps run on fp16 operands (iterate and polynomial factor): the MFMA rate of bf16 with 11
+  // instead of 8 significant bits, so that the rounding of a step, which the weak singular directions amplify by
+  // 1/sigma, is 8 times smaller.  Every entry is at most a few units in magnitude: no range problem.  The
+  // hand-over to the closing steps and the split-plane modes stay bf16 (their planes sum exactly).
+  const int main_f16 = np_main == 1 ? 1 : 0;
   const SegList& seg_main = np_main == 1 ? kSeg1 : (np_main == 2 ? kSeg3 : kSeg6);
   const uint32_t cap = ctx->cfg.polar_max_iters;
   const double tol = ctx->cfg.polar_tol;
@@ -534,14 +574,15 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // keeps it as it goes): a copy of either is taken here, before the statistics are cleared.
   HIP_TRY(launch_polar_start_pack(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, np_main, nullptr,
                                   ctx->PXn[cur], ctx->PXt[cur], plane, ctx->f32 ? 0 : 1,
-                                  ctx->head_fused ? nullptr : ctx->dot_part, ctx->ldot, s));
+                                  ctx->head_fused ? nullptr : ctx->dot_part, ctx->ldot, s, main_f16));
   if (ctx->head_fused) HIP_TRY(hipMemcpyAsync(ctx->ldot, ctx->L, h * sizeof(double), hipMemcpyDeviceToDevice, s));
   int slot = 0;           // next residual-history slot
   uint32_t iters = 0, closing = 0;
 
-  auto gram = [&](const SegList& sl, float ci, float cg, int np_w, bool want_resid) -> hipError_t {
+  auto gram = [&](const SegList& sl, float ci, float cg, int np_w, bool want_resid, int f16 = 0) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
+    g.ab_f16 = f16;
     g.A = ctx->PXt[cur]; g.B = ctx->PXt[cur]; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
     g.M = g.N = g.K = dh;
     g.nseg = sl.n;
@@ -557,9 +598,10 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // X' = X W (+ X): reads the planes in buffer `cur`, writes np_x planes (both layouts)
   // into the other buffer, and the fp32 iterate when asked.
   // np_t < 0: the hand-over form -- the result rounded to -np_t planes, that value in PX and in as many planes of each layout.
-  auto apply = [&](const SegList& sl, const bf16_bits* W, int np_t, int np_n, bool add_x, float* out32) -> hipError_t {
+  auto apply = [&](const SegList& sl, const bf16_bits* W, int np_t, int np_n, bool add_x, float* out32, int f16 = 0) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
+    g.ab_f16 = f16;
     g.A = ctx->PXn[cur]; g.B = W; g.lda = g.ldb = dh; g.batchA = g.batchB = blk;
     g.M = g.N = g.K = dh;
     g.nseg = sl.n;
@@ -630,10 +672,10 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // step and are finished by the closing iterations.)
   int handover_planes = 0;   // 1 / 2: the iterate in PX is exactly the sum of that many planes of buffer `cur`; 0: all three
   auto main_phase = [&](double l0, bool planes_ready) -> conqur_status {
-    if (!planes_ready) HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s));
+    if (!planes_ready) HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s, main_f16));
     const double e_stop = np_main == 1 ? 4e-3 : 5e-4;   // the safety margins below floor the ripple near 2e-4
     double l = l0, u = 1.0;
-    if (dh == 128 && np_main == 1 && iters < cap && !std::getenv("CONQUR_NO_FUSED_POLAR")) {
+    if (dh == 128 && np_main == 1 && iters < cap) {
       // heads of width 128: the whole schedule in one launch, the iterate stays in LDS (head_polar.hip)
       PolarSchedule sc;
       sc.nsteps = 0;
@@ -658,7 +700,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       double a, b;
       const double E = step_cubic(l, u, &a, &b);
       const bool last = E <= e_stop || iters + 1 >= cap;
-      HIP_TRY(gram(seg_main, (float)a, (float)b, np_main, trace));
+      HIP_TRY(gram(seg_main, (float)a, (float)b, np_main, trace, main_f16));
       ++slot;
       // The last main step hands over to the closing iterations.  Its result is rounded to the planes this phase
       // works with anyway (one: 8 bits, two: 16 bits -- a perturbation of the size every step of this phase
@@ -668,7 +710,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       if (last && np_main == 3) {
         HIP_TRY(apply(seg_main, ctx->PW, 3, 2, false, ctx->PX));
       } else {
-        HIP_TRY(apply(seg_main, ctx->PW, last ? -np_main : np_main, last ? -np_main : np_main, false, nullptr));
+        HIP_TRY(apply(seg_main, ctx->PW, last ? -np_main : np_main, last ? -np_main : np_main, false, nullptr, main_f16));
         if (last) handover_planes = np_main;
       }
       ++iters;
@@ -953,12 +995,26 @@ conqur_status conqur_get_state(conqur_ctx* ctx, float* R_host, float* M_host, ui
   const size_t blk = (size_t)ctx->heads * ctx->dh * ctx->dh;
   hipStream_t s = ctx->stream;
   if (R_host) HIP_TRY(hipMemcpyAsync(R_host, ctx->R, blk * sizeof(float), hipMemcpyDeviceToHost, s));
+  if (M_host && ctx->parts_pending) {
+    HIP_TRY(hipSetDevice(ctx->cfg.device));
+    conqur_status st = materialise_m(ctx);
+    if (st != CONQUR_OK) return st;
+  }
   if (M_host) {
     if (ctx->m_empty) std::memset(M_host, 0, blk * sizeof(float));
     else HIP_TRY(hipMemcpyAsync(M_host, ctx->M, blk * sizeof(float), hipMemcpyDeviceToHost, s));
   }
-  std::vector<unsigned long long> rows(ctx->heads);
-  if (n_rows) HIP_TRY(hipMemcpyAsync(rows.data(), ctx->rows, ctx->heads * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+  std::vector<unsigned long long> rows(ctx->heads, 0ull);
+  if (n_rows) {   // the fused per-head step counts in ctx->rows, the general path in the slot counters: both are added
+    std::vector<unsigned long long> buf(ctx->stat_words);
+    HIP_TRY(hipMemcpyAsync(buf.data(), ctx->L, ctx->stat_words * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    const int h = ctx->heads;
+    for (int i = 0; i < h; ++i) {
+      rows[i] = buf[h + i];
+      for (int q = 0; q < kCountSlots; ++q) rows[i] += buf[3 * h + ((size_t)i * kCountSlots + q) * 2];
+    }
+  }
   HIP_TRY(hipStreamSynchronize(s));
   if (M_host && !ctx->m_empty)   // heads stepped in ranges: those without rows still hold the M of before the last update
     for (int i = 0; i < ctx->heads; ++i)
@@ -995,6 +1051,7 @@ conqur_status conqur_set_state(conqur_ctx* ctx, const float* R_host, const float
   }
   if (M_host) {
     HIP_TRY(hipMemcpyAsync(ctx->M, M_host, blk * sizeof(float), hipMemcpyHostToDevice, s));
+    ctx->parts_pending = 0;   // whatever shares were pending are replaced with the rest of M
     ctx->m_empty = false;
     ctx->have_rows = true;
     ctx->h_empty.assign(h, 0);

@@ -13,7 +13,7 @@ namespace conqur {
 enum GemmEpilogue : int {
   EPI_SIGN = 0,  // corner signs, transposed: St[n][m] = +-1 (bf16 or fp16)
   EPI_ACT = 1,   // Y[m][n] = acc, stored as bf16 or fp32 (rotated activations for the quantiser score)
-  EPI_F32 = 2,   // C[m][n] = acc (+ C[m][n] if accumulate), fp32
+  EPI_F32 = 2,   // C[m][n] = out_scale * acc (+ C[m][n] if accumulate), fp32
   EPI_GRAMW = 3, // acc = Gram matrix G: W = coef_i*I + coef_g*G (+ the planes Padd) written as np_out bf16 split
                  // planes (natural layout) and per-wavefront partial sums of (G - I)^2
   EPI_XOUT = 4,  // acc = X' (+ Xadd): written as fp32 (C32) and/or np_out bf16 split planes in natural (Pn)
@@ -35,7 +35,8 @@ struct GemmArgs {
   int64_t lda, ldb;        // row pitch in elements (multiples of 8)
   int64_t batchA, batchB;  // element offset between batch entries (grid.z)
   int M, N, K;             // K per segment, a multiple of 8
-  int ab_f16;              // operands hold fp16 instead of bf16 (EPI_F32 only)
+  int ab_f16;              // operands hold fp16 instead of bf16 (EPI_F32; EPI_GRAMW / EPI_XOUT with one output plane,
+                           // which is then fp16 as well: the single-plane polar steps; EPI_XLAST, whose outputs stay bf16)
   int nseg;
   int64_t a_seg[kMaxSegments];  // element offsets of each K-segment
   int64_t b_seg[kMaxSegments];
@@ -44,6 +45,7 @@ struct GemmArgs {
   int64_t ldc, batchC;     // pitch / batch offset of every output of the epilogue (elements)
   int c_is_f32;            // EPI_ACT: element type of C
   int accumulate;          // EPI_F32: add to C instead of overwriting
+  float out_scale;         // EPI_F32: C = out_scale * acc (+ C)
   int64_t st_rows_valid;   // EPI_SIGN: St rows hold this many m entries (padded pitch), multiple of 4
   int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
   double* resid_part;      // EPI_GRAMW: [batch][gemm_num_partials()] per-wavefront sums of (acc - I)^2, or null.

@@ -340,7 +340,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
           if (m >= g.M) continue;
           float* p = C + (int64_t)m * g.ldc + n;
-          *p = g.accumulate ? (*p + acc[i][j][e]) : acc[i][j][e];
+          const float v = g.out_scale * acc[i][j][e];
+          *p = g.accumulate ? (*p + v) : v;
         }
       }
   } else if constexpr (EPI == EPI_GRAMW) {
@@ -369,12 +370,17 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
             const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
             for (int p = 0; p < g.np_add; ++p) w[r] += bf16_to_f32(g.Padd[p * g.plane_out + off]);
           }
-          for (int p = 0; p < g.np_out; ++p) {
+          for (int p = 0; p < (F16 ? 1 : g.np_out); ++p) {
             uint2 t;
-            t.x = f32x2_to_bf16x2(w[0], w[1]);
-            t.y = f32x2_to_bf16x2(w[2], w[3]);
-            w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
-            w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
+            if constexpr (F16) {   // fp16 operands: the factor is one fp16 plane
+              t.x = f32x2_to_f16x2(w[0], w[1]);
+              t.y = f32x2_to_f16x2(w[2], w[3]);
+            } else {
+              t.x = f32x2_to_bf16x2(w[0], w[1]);
+              t.y = f32x2_to_bf16x2(w[2], w[3]);
+              w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
+              w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
+            }
             bf16_bits* pn = g.Pn + p * g.plane_out + boff + (int64_t)mb * g.ldc + n;
             pn[0] = (bf16_bits)t.x; pn[g.ldc] = (bf16_bits)(t.x >> 16);
             pn[2 * g.ldc] = (bf16_bits)t.y; pn[3 * g.ldc] = (bf16_bits)(t.y >> 16);
@@ -525,13 +531,18 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
             if (g.Xadd) v[r] += g.Xadd[off];
             if (g.C32) g.C32[off] = v[r];
           }
-          const int np_max = g.np_out > g.np_out_n ? g.np_out : g.np_out_n;
+          const int np_max = F16 ? 1 : (g.np_out > g.np_out_n ? g.np_out : g.np_out_n);
           for (int p = 0; p < np_max; ++p) {
             uint2 t;   // the 4 values as bf16, packed; the remainder goes on to the next plane
-            t.x = f32x2_to_bf16x2(v[0], v[1]);
-            t.y = f32x2_to_bf16x2(v[2], v[3]);
-            v[0] -= __uint_as_float(t.x << 16); v[1] -= __uint_as_float(t.x & 0xffff0000u);
-            v[2] -= __uint_as_float(t.y << 16); v[3] -= __uint_as_float(t.y & 0xffff0000u);
+            if constexpr (F16) {   // fp16 operands: the iterate is one fp16 plane of each layout
+              t.x = f32x2_to_f16x2(v[0], v[1]);
+              t.y = f32x2_to_f16x2(v[2], v[3]);
+            } else {
+              t.x = f32x2_to_bf16x2(v[0], v[1]);
+              t.y = f32x2_to_bf16x2(v[2], v[3]);
+              v[0] -= __uint_as_float(t.x << 16); v[1] -= __uint_as_float(t.x & 0xffff0000u);
+              v[2] -= __uint_as_float(t.y << 16); v[3] -= __uint_as_float(t.y & 0xffff0000u);
+            }
             if (p < g.np_out_n) {
               bf16_bits* q = g.Pn + p * g.plane_out + boff + (int64_t)mb * g.ldc + n;
               q[0] = (bf16_bits)t.x; q[g.ldc] = (bf16_bits)(t.x >> 16);
@@ -630,7 +641,9 @@ int gemm_num_workgroups(int M, int N, int batch) {
 
 hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStream_t stream) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || (a.K & 7) || (a.lda & 7) || (a.ldb & 7) || a.nseg < 1 || a.nseg > kMaxSegments ||
-      batch < 1 || (a.ab_f16 && epi != EPI_F32) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
+      batch < 1 || (a.ab_f16 && epi != EPI_F32 && epi != EPI_GRAMW && epi != EPI_XOUT && epi != EPI_XLAST) ||
+      (a.ab_f16 && ((epi == EPI_GRAMW && (a.np_out != 1 || a.np_add != 0)) ||
+                    (epi == EPI_XOUT && (a.np_out != 1 || a.np_out_n != 1 || a.Xadd || a.C32)))) || (int64_t)a.M * a.lda >= (1ll << 30) || (int64_t)a.N * a.ldb >= (1ll << 30))
     return hipErrorInvalidValue;
   if (a.symmetric && ((epi != EPI_GRAMW && epi != EPI_SQUARE && epi != EPI_FRO2) || (epi != EPI_FRO2 && a.A != a.B) ||
                       a.M != a.N || a.lda != a.ldb || (a.M & 3)))
@@ -640,9 +653,9 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
     case EPI_ACT: return launch_epi<EPI_ACT>(a, batch, stream);
     case EPI_F32: return a.ab_f16 ? launch_epi<EPI_F32, true>(a, batch, stream) : launch_epi<EPI_F32>(a, batch, stream);
-    case EPI_GRAMW: return launch_epi<EPI_GRAMW>(a, batch, stream);
-    case EPI_XLAST: return launch_epi<EPI_XLAST>(a, batch, stream);
-    case EPI_XOUT: return launch_epi<EPI_XOUT>(a, batch, stream);
+    case EPI_GRAMW: return a.ab_f16 ? launch_epi<EPI_GRAMW, true>(a, batch, stream) : launch_epi<EPI_GRAMW>(a, batch, stream);
+    case EPI_XLAST: return a.ab_f16 ? launch_epi<EPI_XLAST, true>(a, batch, stream) : launch_epi<EPI_XLAST>(a, batch, stream);
+    case EPI_XOUT: return a.ab_f16 ? launch_epi<EPI_XOUT, true>(a, batch, stream) : launch_epi<EPI_XOUT>(a, batch, stream);
     case EPI_SQUARE: return launch_epi<EPI_SQUARE>(a, batch, stream);
     case EPI_FRO2: return launch_epi<EPI_FRO2>(a, batch, stream);
   }

@@ -1,11 +1,12 @@
 // Main phase of the polar iteration for heads of width 128, one launch for all steps
 // (the composed cubics X <- X (a_k I + b_k X^T X) of the Procrustes update, Sec. 3.3).
 //
-// At this width the iterate (32 KiB as bf16, natural and transposed), and the
+// At this width the iterate (32 KiB as fp16, natural and transposed), and the
 // polynomial factor W (32 KiB) live in the LDS of one compute unit, so a workgroup
 // per head runs the whole schedule without touching HBM between steps; the general
 // path needs two GEMM launches per step, which at 128 x 128 are launch latency only.
-// Per step, with every product a 32x32x16 bf16 MFMA on K-contiguous operands:
+// Per step, with every product a 32x32x16 fp16 MFMA on K-contiguous operands (the iterate and the factor are held as
+// fp16: 11 significant bits at the rate of bf16's 8; every entry is at most a few units in magnitude):
 //   G = X^T X            A = B = X^T                     -> W = a I + b G, bf16, to LDS
 //   X' = X W             A = X,  B = W (symmetric)       -> accumulators hold X'   : packed stores give X'^T
 //   X'^T = W X^T         A = W,  B = X                   -> accumulators hold X'^T : packed stores give X'
@@ -48,7 +49,7 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
   __syncthreads();
 
   auto frag = [&](const unsigned char* base, int row, int kk) {
-    return *reinterpret_cast<const bf16x8*>(base + loff(row, 2 * kk + half));
+    return *reinterpret_cast<const f16x8*>(base + loff(row, 2 * kk + half));
   };
   // acc[i][j] = sum_k A[rowA + 32 i + .][k] B[rowB + 32 j + .][k]
   auto product = [&](const unsigned char* A, int rowA, const unsigned char* B, int rowB, f32x16 (&acc)[2][2]) {
@@ -60,7 +61,7 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 #pragma unroll
     for (int kk = 0; kk < DH / 16; ++kk) {
-      bf16x8 fa[2], fb[2];
+      f16x8 fa[2], fb[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) fa[i] = frag(A, rowA + 32 * i + col, kk);
 #pragma unroll
@@ -68,7 +69,7 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
   };
   // Element e = 4 jj + ii of acc[i][j]: row m = rowA + 32 i + 8 jj + 4 half + ii, column n = rowB + 32 j + col.
@@ -86,8 +87,8 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
 #pragma unroll
           for (int ii = 0; ii < 4; ++ii) v[ii] = cg * acc[i][j][4 * jj + ii] + ((m0 + ii == n) ? ci : 0.0f);
           uint2 pk;
-          pk.x = f32x2_to_bf16x2(v[0], v[1]);
-          pk.y = f32x2_to_bf16x2(v[2], v[3]);
+          pk.x = f32x2_to_f16x2(v[0], v[1]);
+          pk.y = f32x2_to_f16x2(v[2], v[3]);
           *reinterpret_cast<uint2*>(dst + loff(n, m0 >> 3) + (m0 & 7) * 2) = pk;
         }
       }

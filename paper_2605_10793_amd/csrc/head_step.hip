@@ -6,13 +6,14 @@
 // fp32 accumulators) live on one compute unit, so the step is bound by reading X once
 // (256 bytes per token and head) instead of by GEMM launches: a workgroup owns one
 // head and one contiguous share of the tokens, keeps R_h^T in LDS and M_h in MFMA
-// accumulators, and streams 64-token tiles:
+// accumulators, and streams 128-token tiles through 16 wavefronts (the per-tile work is a
+// chain of short, latency-bound phases; wider tiles halve the number of chains):
 //   1. tile -> registers (16-byte loads, prefetched one tile ahead), row norms by
 //      16-lane shuffles, natural copy to LDS;
 //   2. Y = X R_h (32x32x16 bf16 MFMA; A = X tile, B = R_h^T), in flight with the scaled
 //      transposed copy x^ (fp16) of the tile; from the accumulators: the corner signs,
 //      written transposed (+-1 as fp16) to LDS;
-//   3. M_h += x^^T C (32x32x16 fp16 MFMA, contraction over the tile's 64 tokens).
+//   3. M_h += x^^T C (32x32x16 fp16 MFMA, contraction over the tile's 128 tokens).
 // Each workgroup ends by storing its partial M_h; k_head_reduce adds the shares in a
 // fixed order.  Rows that are zero or non-finite are skipped exactly as in k_row_norms.
 #include "kernels.h"
@@ -22,16 +23,18 @@ namespace conqur {
 namespace {
 
 constexpr int DH = 128;        // head width
-constexpr int TT = 64;         // tokens per tile
+constexpr int TT = 128;        // tokens per tile
+constexpr int NTHREADS = 1024; // 16 wavefronts
 constexpr int XROW = 256;      // bytes per natural row (128 bf16), 16 chunks of 16 bytes, XOR swizzled
-constexpr int TROW = 144;      // bytes per transposed row (64 fp16 + 8 pad): ds_read_b128 of 16 consecutive rows hits 64 banks
+constexpr int TROW = 272;      // bytes per transposed row (128 fp16 + 8 pad): ds_read_b128 of 16 consecutive rows hits 64 banks
 
 constexpr int kSmemBytes = DH * XROW + TT * XROW + 2 * DH * TROW;
+constexpr float kOutScale = 1.0f / (kXhatScale * 11.313708498984761f);   // the operand carries kXhatScale x^, the corner 1/sqrt(128)
 
 __device__ __forceinline__ int xoff(int row, int chunk) { return row * XROW + ((chunk ^ (row & 15)) << 4); }
 
 template <bool STORE_SIGNS>
-__global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restrict__ X, int64_t T, int64_t stride, int heads,
+__global__ void __launch_bounds__(NTHREADS) k_head_step128(const bf16_bits* __restrict__ X, int64_t T, int64_t stride, int heads,
                                                       const bf16_bits* __restrict__ RopT, float* __restrict__ Mpart,
                                                       int64_t tokens_per_split, float* __restrict__ nrm, int64_t ldn,
                                                       double* __restrict__ L, unsigned long long* __restrict__ rows,
@@ -42,8 +45,8 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
   unsigned char* const sX = sR + DH * XROW;              // tile, natural: row token, K = channel
   unsigned char* const sXt = sX + TT * XROW;             // x^ transposed (fp16): row channel, K = token
   unsigned char* const sCt = sXt + DH * TROW;            // corner signs transposed (fp16): row n, K = token
-  __shared__ float sW[2][TT];      // 1/(||x|| sqrt(dh)) per token of the tile (0: skipped), by tile parity
-  __shared__ double shd[8];
+  __shared__ float sW[2][TT];      // kXhatScale / ||x|| per token of the tile (0: skipped), by tile parity
+  __shared__ double shd[16];
 
   const int h = blockIdx.x, sp = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -56,33 +59,31 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
   {
     const bf16_bits* Rh = RopT + (int64_t)h * DH * DH;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int idx = q * 512 + tid, row = idx >> 4, chunk = idx & 15;
+    for (int q = 0; q < 2; ++q) {
+      const int idx = q * NTHREADS + tid, row = idx >> 4, chunk = idx & 15;
       *reinterpret_cast<uint4*>(sR + xoff(row, chunk)) = *reinterpret_cast<const uint4*>(Rh + row * DH + chunk * 8);
     }
   }
 
-  // Thread -> tile element map of phase 1: row (token) lrow + 32 q, chunk lchunk: the 16 lanes of a row sit in one wavefront.
+  // Thread -> tile element map of phase 1: row (token) lrow + 64 q, chunk lchunk: the 16 lanes of a row sit in one wavefront.
   const int lrow = tid >> 4, lchunk = tid & 15;
   const bf16_bits* Xh = X + (int64_t)h * DH + lchunk * 8;
   uint4 cur[2], nxt[2];
   auto load_tile = [&](int tile, uint4* dst) {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int64_t t = t_begin + (int64_t)tile * TT + lrow + 32 * q;
+      const int64_t t = t_begin + (int64_t)tile * TT + lrow + 64 * q;
       dst[q] = (tile < ntiles && t < t_end) ? *reinterpret_cast<const uint4*>(Xh + t * stride) : make_uint4(0u, 0u, 0u, 0u);
     }
   };
   load_tile(0, cur);
 
-  // 8 wavefronts (2 per SIMD, so that one's LDS and conversion work runs beside the other's MFMAs).
+  // 16 wavefronts (4 per SIMD, so that one's LDS and conversion work runs beside the others' MFMAs).
   const int ti = wave >> 2, nb = wave & 3;        // rotate: tokens [32 ti, +32) x columns [32 nb, +32)
-  const int rm = wave >> 1, cn = 2 * (wave & 1);  // accumulate: channels [32 rm, +32) x columns [32 cn, +64)
-  f32x16 accM[2];
+  const int rm = wave >> 2, cn = wave & 3;        // accumulate: channels [32 rm, +32) x columns [32 cn, +32)
+  f32x16 accM;
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) accM[j][e] = 0.0f;
+  for (int e = 0; e < 16; ++e) accM[e] = 0.0f;
   double l_acc = 0.0;
   unsigned n_rows = 0, n_skipped = 0;
 
@@ -91,7 +92,7 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
     // ---- phase 1: norms, natural copy
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int r = lrow + 32 * q;
+      const int r = lrow + 64 * q;
       const int64_t t = t_begin + (int64_t)tile * TT + r;
       const uint4 v = cur[q];
       float ss = 0.0f;
@@ -114,7 +115,7 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
             ++n_skipped;
           } else if (ss > 0.0f) {
             n = sqrtf(ss);
-            w = 1.0f / (n * sqrtf((float)DH));
+            w = kXhatScale / n;
             ++n_rows;
           } else {
             ++n_skipped;
@@ -128,9 +129,9 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
     __syncthreads();
 
     // ---- phase 2a: scaled transposed copy x^ (fp16).  Thread = (token pair p, chunk g): 4-byte LDS writes whose
-    // banks differ across the 32 token pairs of a wavefront.
+    // banks differ across the 64 token pairs of a wavefront.
     {
-      const int p = tid & 31, g = tid >> 5;
+      const int p = tid & 63, g = tid >> 6;
       const float w0 = sW[par][2 * p], w1 = sW[par][2 * p + 1];
       {
         const int chunk = g;
@@ -182,15 +183,12 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
     }
     __syncthreads();
 
-    // ---- phase 3: M_h += x^^T C.  Wavefront (rm, cn) owns channels [32 rm, +32) x columns [32 cn, +64) of M_h.
+    // ---- phase 3: M_h += x^^T C.  Wavefront (rm, cn) owns channels [32 rm, +32) x columns [32 cn, +32) of M_h.
 #pragma unroll
     for (int kk = 0; kk < TT / 16; ++kk) {
       const f16x8 fa = *reinterpret_cast<const f16x8*>(sXt + (32 * rm + col) * TROW + (2 * kk + half) * 16);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const f16x8 fb = *reinterpret_cast<const f16x8*>(sCt + (32 * (cn + j) + col) * TROW + (2 * kk + half) * 16);
-        accM[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, accM[j], 0, 0, 0);
-      }
+      const f16x8 fb = *reinterpret_cast<const f16x8*>(sCt + (32 * cn + col) * TROW + (2 * kk + half) * 16);
+      accM = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, accM, 0, 0, 0);
     }
 #pragma unroll
     for (int q = 0; q < 2; ++q) cur[q] = nxt[q];
@@ -205,15 +203,15 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
   {
     float* Mp = Mpart + ((int64_t)sp * heads + h) * DH * DH;
     float dot = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = 32 * (cn + j) + col;
+    {
+      const int n = 32 * cn + col;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int m = 32 * rm + 8 * (e >> 2) + 4 * half + (e & 3);
-        Mp[m * DH + n] = accM[j][e];
+        const float mv = accM[e] * kOutScale;
+        Mp[m * DH + n] = mv;
         const bf16_bits r = *reinterpret_cast<const bf16_bits*>(sR + xoff(n, m >> 3) + (m & 7) * 2);   // R_op[m][n]
-        dot += accM[j][e] * bf16_to_f32(r);
+        dot += mv * bf16_to_f32(r);
       }
     }
     l_acc = (double)dot * 11.313708498984761;   // sqrt(128)
@@ -225,15 +223,16 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
     __syncthreads();
     if (lane == 0) shd[wave] = l_acc;
     __syncthreads();
-    const double lt = shd[0] + shd[1] + shd[2] + shd[3] + shd[4] + shd[5] + shd[6] + shd[7];
+    auto total = [&]() { double t = 0.0; for (int i = 0; i < NTHREADS / 64; ++i) t += shd[i]; return t; };
+    const double lt = total();
     __syncthreads();
     if (lane == 0) shd[wave] = r;
     __syncthreads();
-    const double rt = shd[0] + shd[1] + shd[2] + shd[3] + shd[4] + shd[5] + shd[6] + shd[7];
+    const double rt = total();
     __syncthreads();
     if (lane == 0) shd[wave] = k;
     __syncthreads();
-    const double kt = shd[0] + shd[1] + shd[2] + shd[3] + shd[4] + shd[5] + shd[6] + shd[7];
+    const double kt = total();
     if (tid == 0) {
       atomicAdd(L + h, lt);
       atomicAdd(rows + h, (unsigned long long)rt);
@@ -242,11 +241,13 @@ __global__ void __launch_bounds__(512) k_head_step128(const bf16_bits* __restric
   }
 }
 
-// M[h] (+)= sum over shares of Mpart[share][h], fixed order.
+// M[h] (+)= sum over shares of Mpart[share][h], fixed order.  FRO2: also the sum of squares of the block's 1024 results
+// (one double per workgroup, fro2_part[blockIdx.x]; a head is DH * DH / 1024 = 16 consecutive workgroups), so that the
+// update that follows needs no separate pass over M for ||M_h||_F.
+template <bool FRO2>
 __global__ void __launch_bounds__(256) k_head_reduce(const float* __restrict__ Mpart, int nsplit, int64_t n_total,
-                                                     float* __restrict__ M, int accumulate) {
-  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-  if (i >= n_total) return;
+                                                     float* __restrict__ M, int accumulate, double* __restrict__ fro2_part) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;   // n_total is a multiple of 1024: no ragged block
   float4 acc = accumulate ? *reinterpret_cast<const float4*>(M + i) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   for (int s0 = 0; s0 < nsplit; s0 += 8) {   // eight shares' loads in flight, added in share order
     float4 v[8];
@@ -257,6 +258,14 @@ __global__ void __launch_bounds__(256) k_head_reduce(const float* __restrict__ M
     for (int u = 0; u < 8; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
   }
   *reinterpret_cast<float4*>(M + i) = acc;
+  if constexpr (FRO2) {
+    __shared__ double sh[4];
+    double q = (double)acc.x * acc.x + (double)acc.y * acc.y + (double)acc.z * acc.z + (double)acc.w * acc.w;
+    q = wave_sum_d(q);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = q;
+    __syncthreads();
+    if (threadIdx.x == 0) fro2_part[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+  }
 }
 
 }  // namespace
@@ -288,18 +297,21 @@ hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, in
   });
   if (e != hipSuccess) return e;
   if (St)
-    hipLaunchKernelGGL(k_head_step128<true>, grid, dim3(512), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
+    hipLaunchKernelGGL(k_head_step128<true>, grid, dim3(NTHREADS), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
                        L, rows, skipped, nonfinite, St, pitch);
   else
-    hipLaunchKernelGGL(k_head_step128<false>, grid, dim3(512), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
+    hipLaunchKernelGGL(k_head_step128<false>, grid, dim3(NTHREADS), kSmemBytes, s, X, T, stride, heads, RopT, Mpart, tokens_per_split, nrm, ldn,
                        L, rows, skipped, nonfinite, St, pitch);
   return hipGetLastError();
 }
 
-hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, hipStream_t s) {
+hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, double* fro2_part, hipStream_t s) {
   const int64_t n_total = (int64_t)heads * DH * DH;
-  hipLaunchKernelGGL(k_head_reduce, dim3((unsigned)((n_total / 4 + 255) / 256)), dim3(256), 0, s, Mpart, nsplit, n_total, M,
-                     accumulate);
+  const dim3 grid((unsigned)(n_total / 1024));
+  if (fro2_part)
+    hipLaunchKernelGGL(k_head_reduce<true>, grid, dim3(256), 0, s, Mpart, nsplit, n_total, M, accumulate, fro2_part);
+  else
+    hipLaunchKernelGGL(k_head_reduce<false>, grid, dim3(256), 0, s, Mpart, nsplit, n_total, M, accumulate, fro2_part);
   return hipGetLastError();
 }
 

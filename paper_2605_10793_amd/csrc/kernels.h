@@ -7,7 +7,7 @@
 
 namespace conqur {
 
-// n_i = ||x_i||_2 over each head slice; w_i = 1/(n_i*sqrt(dh)), or 0 for a row that is
+// n_i = ||x_i||_2 over each head slice; w_i = kXhatScale / n_i, or 0 for a row that is
 // all zero or holds a non-finite value (then nrm = 0 and *nonfinite is raised for NaN/Inf).
 hipError_t launch_row_norms(const void* X, int x_is_f32, int64_t T, int64_t stride, int heads, int dh,
                             float* nrm, float* w, int64_t ldn, int* nonfinite, hipStream_t s);
@@ -27,8 +27,9 @@ hipError_t launch_split_rows(const float* X, int64_t T, int64_t stride, int d, b
 
 // Split an fp32 matrix batch [batch][rows][cols] into np bf16 planes, in natural
 // layout (outN[p][b][r][c]) and/or transposed (outT[p][b][c][r]); either may be null.
+// out_f16 (np = 1 only): the plane holds the values rounded to fp16 instead of bf16.
 hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
-                       int64_t plane, hipStream_t s);
+                       int64_t plane, hipStream_t s, int out_f16 = 0);
 
 // out[h] = <R_op,h , M_h> over n elements per head, R_op = R rounded to bf16 if round_bf16 else R (the l1 term of
 // the accumulated rows is sqrt(dh) times this).  part: heads * dot_rm_partials(n) doubles of scratch.
@@ -46,7 +47,7 @@ hipError_t launch_fro2(const float* M, int heads, int64_t n, double* part, doubl
 // round_bf16), the quantity of launch_dot_rm, from the same pass.
 hipError_t launch_polar_start_pack(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, int np,
                                    float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, int round_bf16,
-                                   double* dot_part, double* dot_out, hipStream_t s);
+                                   double* dot_part, double* dot_out, hipStream_t s, int out_f16 = 0);
 
 // X += kappa * R over n elements (all heads).
 hipError_t launch_axpy(float* X, const float* R, int64_t n, float kappa, hipStream_t s);
@@ -61,16 +62,21 @@ hipError_t launch_polar_finish_pack(const float* X, const float* M, int heads, i
 // takes the corners and accumulates; every workgroup (head, share of the tokens) stores a partial M_h into
 // Mpart [nsplit][heads][128][128], adds its share of L / rows / skipped, writes the row norms and, if St is not null,
 // the corner signs (+-1 as fp16, transposed [heads*128][pitch]).  launch_head_reduce then sets or adds the shares to M.
+// The partial M_h already carry the factor 1 / (kXhatScale sqrt(128)).
 int head_step_splits(int heads, int64_t T);
 hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, int heads, const bf16_bits* RopT, float* Mpart,
                                int nsplit, float* nrm, int64_t ldn, double* L, unsigned long long* rows,
                                unsigned long long* skipped, int* nonfinite, bf16_bits* St, int64_t pitch, hipStream_t s);
-hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, hipStream_t s);
+// fro2_part non-null: also 16 partial sums of squares per head of the resulting M (kHeadReduceParts doubles per head, in
+// head order), whose sum per head is ||M_h||_F^2.
+constexpr int kHeadReduceParts = 16;
+hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, double* fro2_part, hipStream_t s);
 
 // Main phase of the polar iteration for heads of width 128 in one launch (head_polar.hip): runs the composed cubics
 // X <- X (a_k I + b_k X^T X), k < nsteps, on single bf16 operand planes held in LDS.  Xn0 / Xt0: the start iterate as
 // one natural and one transposed bf16 plane [heads][128][128].  Outputs, as the last step of the general path writes them:
 // the result rounded to bf16, as X32 (fp32), Pt (one transposed plane) and Pn (one natural plane).
+// The start planes hold fp16 (the steps run on fp16 operands, 11 significant bits); the outputs are bf16.
 constexpr int kPolarScheduleMax = 64;
 struct PolarSchedule {
   int nsteps;

@@ -87,7 +87,7 @@ __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, i
       atomicOr(nonfinite, 1);
     } else if (ss > 0.0f) {
       n = sqrtf(ss);
-      wi = 1.0f / (n * sqrtf((float)dh));
+      wi = kXhatScale / n;
     }
     nrm[(int64_t)h * ldn + i] = n;
     w[(int64_t)h * ldn + i] = wi;
@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(256) k_transpose_scale(const void* __restrict_
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        if constexpr (NP == 1) tile[r][c * 8 + e] = f32_to_f16(f[e]);   // |x^| <= 1: fp16 keeps 11 significant bits
+        if constexpr (NP == 1) tile[r][c * 8 + e] = f32_to_f16(f[e]);   // |x^| kXhatScale <= 64: fp16 keeps 11 significant bits
         else tile[r][c * 8 + e] = f[e];
       }
     }
@@ -220,6 +220,7 @@ struct PackFused {
   double* dot_part;       // DOT: [batch][gridDim.y * gridDim.x]; START: same for <R_op, M>, or null
   int round_bf16;         // START: R_op is src2 rounded to bf16
   float* out32;           // may be null
+  int out_f16;            // NP == 1 only: the plane holds fp16 instead of bf16
 };
 
 template <int NP, bool START, bool DOT>
@@ -273,7 +274,10 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
       if (outN) {
         bf16_bits p[4][NP];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) split_bf16<NP>(f[e], p[e]);
+        for (int e = 0; e < 4; ++e) {
+          if (NP == 1 && fx.out_f16) p[e][0] = f32_to_f16(f[e]);
+          else split_bf16<NP>(f[e], p[e]);
+        }
 #pragma unroll
         for (int q = 0; q < NP; ++q) {
           uint2 o;
@@ -299,7 +303,10 @@ __global__ void __launch_bounds__(256) k_pack(const float* __restrict__ src, int
     if (c0 + cl >= cols || r0 + rc >= rows) continue;
     bf16_bits p[8][NP];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) split_bf16<NP>(tile[rc + e][cl], p[e]);
+    for (int e = 0; e < 8; ++e) {
+      if (NP == 1 && fx.out_f16) p[e][0] = f32_to_f16(tile[rc + e][cl]);
+      else split_bf16<NP>(tile[rc + e][cl], p[e]);
+    }
 #pragma unroll
     for (int q = 0; q < NP; ++q) {
       uint4 v;
@@ -638,8 +645,10 @@ static hipError_t launch_pack_impl(const float* src, int batch, int rows, int co
 }
 
 hipError_t launch_pack(const float* src, int batch, int rows, int cols, int np, bf16_bits* outN, bf16_bits* outT,
-                       int64_t plane, hipStream_t s) {
+                       int64_t plane, hipStream_t s, int out_f16) {
+  if (out_f16 && np != 1) return hipErrorInvalidValue;
   PackFused fx{};
+  fx.out_f16 = out_f16;
   return launch_pack_impl<false, false>(src, batch, rows, cols, np, outN, outT, plane, fx, s);
 }
 
@@ -647,8 +656,10 @@ int pack_dot_partials(int dh) { return ((dh + 63) / 64) * ((dh + 63) / 64); }
 
 hipError_t launch_polar_start_pack(const float* M, const float* R, int heads, int dh, float lambda, const double* fro2, int np,
                                    float* X32, bf16_bits* outN, bf16_bits* outT, int64_t plane, int round_bf16,
-                                   double* dot_part, double* dot_out, hipStream_t s) {
+                                   double* dot_part, double* dot_out, hipStream_t s, int out_f16) {
+  if (out_f16 && np != 1) return hipErrorInvalidValue;
   PackFused fx{};
+  fx.out_f16 = out_f16;
   fx.src2 = R; fx.fro2 = fro2; fx.lambda = lambda; fx.dh = dh; fx.out32 = X32;
   fx.dot_part = dot_part; fx.round_bf16 = round_bf16;
   hipError_t e = launch_pack_impl<true, false>(M, heads, dh, dh, np, outN, outT, plane, fx, s);

@@ -127,6 +127,12 @@ def batch(w: Workload, b: int, tokens: Optional[int] = None) -> np.ndarray:
     return x
 
 
+def iid_row_indices(seed: int, update: int, n_pool: int, n_rows: int) -> np.ndarray:
+    """Row indices (int64, with replacement) of the stored activations that update number `update` of the offline
+    variant draws (Sec. 4.4: the stored activations are sampled i.i.d. during optimisation)."""
+    return _rng(seed, 6, update).integers(0, n_pool, size=n_rows, dtype=np.int64)
+
+
 def initial_rotation(w: Workload) -> np.ndarray:
     """R0: [heads, dh, dh] float32, Haar-distributed per head.
 

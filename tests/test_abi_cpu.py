@@ -35,6 +35,31 @@ def test_config_struct_matches_header_field_order():
     assert ctypes.sizeof(binding.Config) == 10 * 4 + 8   # ten 32-bit fields, one pointer
 
 
+def test_stats_structs_match_header_field_order():
+    text = open(os.path.join(ROOT, "include", "conqur.h")).read()
+    for cname, cls in (("conqur_batch_stats", binding.BatchStats), ("conqur_update_stats", binding.UpdateStats)):
+        end = text.index("} %s;" % cname)
+        body = text[text.rindex("typedef struct {", 0, end):end]
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        fields = re.findall(r"\b(?:uint64_t|uint32_t|double)\s+([a-z_0-9]+);", body)
+        assert fields == [f[0] for f in cls._fields_], cname
+    assert ctypes.sizeof(binding.BatchStats) == 32 and ctypes.sizeof(binding.UpdateStats) == 56
+
+
+def test_binding_holds_no_method_arithmetic():
+    """The binding marshals arguments; Eq. 1 (the objective) comes from the library's conqur_batch_stats."""
+    src = open(os.path.join(ROOT, "paper_2605_10793_amd", "binding.py")).read()
+    assert "sqrt" not in src
+
+
+def test_oversized_contexts_are_rejected_at_init():
+    lib = binding.load()
+    out = ctypes.c_void_p()
+    R0 = np.eye(16, dtype=np.float32)
+    big = binding.Config(8192, 1, binding.BF16, 1 << 20, 0.0, 0.0, 0, 0, 0, 0, None)   # 8192 * 2^20 operand elements
+    assert lib.conqur_init(ctypes.byref(big), R0.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == binding.EINVAL
+
+
 def test_null_arguments_are_rejected_without_a_device():
     lib = binding.load()
     out = ctypes.c_void_p()

@@ -5,8 +5,11 @@ c2 / c3 (d = 3072 / 4096, 2048 tokens): one whole batch goes through the oracle 
 element by element; the Procrustes update (a 4096^2 Jacobi SVD is out of reach) is
 checked through properties that characterise the polar factor at any size:
 R orthogonal, R^T A symmetric positive semidefinite, <R, A> equal to the nuclear norm.
-c5 (d = 8192, 4096 tokens): the oracle handles a sample of token rows (signs, l1 term);
-M is tied to them by the identity <R_op, M> = L / sqrt(d), which holds at any size.
+After the update the learned rotation goes into the oracle's state and the NEXT batch is stepped on both sides
+(the first batch runs under the Haar R0 only).
+c5 (d = 8192, 4096 tokens): the same, the oracle stepping the whole 4096 x 8192 batch (about 15 s on 16 cores).
+Planted polar factors A = Q P at d = 4096 and 8192 pin the update in closed form, in the configuration the
+benchmark times (prox_lambda = 0.1) and at lambda -> 0+.
 """
 import math
 
@@ -48,7 +51,34 @@ def polar_properties(R, A, tag):
     assert orth <= 1e-4
     assert abs(got - nuc) <= 1e-3 * nuc
     assert ev[0] >= -1e-3 * ev[-1]
+    # R^T A is symmetric for the exact polar factor.  The default single-plane main phase leaves R loose on the
+    # directions with small singular values (rounding there is amplified by 1/sigma); those carry little of A, so the
+    # asymmetry stays small relative to ||R^T A||_F: measured 0.9e-2 .. 3e-2 at d = 3072 .. 8192.
+    assert asym <= 5e-2
     return asym
+
+
+def step_and_compare(cal, oc, B, X, w, tag):
+    """One whole batch on both sides from identical state: M, corner signs, l1 term, row count."""
+    T = X.shape[0]
+    Y, S = oc.step_batch(X, True, True)
+    Xd = B.to_device(X, w.dtype)
+    cal.step_batch(Xd)
+    _, Mg, _ = cal.get_state(want_R=False)
+    Sg, nrm = cal.last_corners(T)
+    relM = np.linalg.norm(Mg[0] - oc.M[0]) / np.linalg.norm(oc.M[0])
+    big = np.abs(Y) > 1e-3 * np.linalg.norm(Y, axis=1, keepdims=True)
+    mism = (Sg != S) & big
+    st = cal.batch_stats()[0]
+    say(f"  {tag}: relM={relM:.2e} sign mismatches {mism.sum()} of {big.sum()} significant, {(Sg != S).sum()} of all; "
+        f"L gpu={st['l1']:.6e} oracle={oc.L[0]:.6e} objective gpu={st['objective']:.6e} oracle={oc.objective()[0]:.6e}")
+    assert relM <= 1e-3
+    assert mism.sum() <= 1e-4 * big.sum()
+    assert st["rows"] == oc.n[0] and st["skipped"] == 0
+    assert abs(st["l1"] - oc.L[0]) <= 1e-3 * oc.L[0]
+    assert abs(st["objective"] - oc.objective()[0]) <= 1e-3 * abs(oc.objective()[0])
+    assert np.allclose(nrm[0], np.linalg.norm(X.astype(np.float64), axis=1), rtol=1e-5)
+    return Xd, Mg
 
 
 @pytest.mark.parametrize("name", ["c2", "c3"])
@@ -59,25 +89,9 @@ def test_full_batch_elementwise(B, name):
     X = I.batch(w, 0)
     oc = O.OracleCalibrator(d, 1, w.dtype, R0, w.prox_lambda)
     say(f"  {name}: oracle step_batch on {T} x {d} ...")
-    Y, S = oc.step_batch(X, True, True)
     cal = B.Calibrator(d, 1, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
     try:
-        Xd = B.to_device(X, w.dtype)
-        cal.step_batch(Xd)
-        _, Mg, _ = cal.get_state(want_R=False)
-        Sg, nrm = cal.last_corners(T)
-        relM = np.linalg.norm(Mg[0] - oc.M[0]) / np.linalg.norm(oc.M[0])
-        big = np.abs(Y) > 1e-3 * np.linalg.norm(Y, axis=1, keepdims=True)
-        mism = (Sg != S) & big
-        all_mism = (Sg != S).sum()
-        st = cal.batch_stats()[0]
-        say(f"  {name}: relM={relM:.2e} sign mismatches {mism.sum()} of {big.sum()} significant, {all_mism} of all; "
-            f"L gpu={st['l1']:.6e} oracle={oc.L[0]:.6e}")
-        assert relM <= 1e-3
-        assert mism.sum() <= 1e-4 * big.sum()
-        assert st["rows"] == oc.n[0] and st["skipped"] == 0
-        assert abs(st["l1"] - oc.L[0]) <= 1e-3 * oc.L[0]
-        assert np.allclose(nrm[0], np.linalg.norm(X.astype(np.float64), axis=1), rtol=1e-5)
+        Xd, _ = step_and_compare(cal, oc, B, X, w, f"{name} batch 0 (Haar R0)")
         say(f"  {name}: oracle quant_error ...")
         so, eo, _, _ = oc.quant_error(X, 4)
         sg, eg = cal.quant_error(Xd, 4)
@@ -111,53 +125,34 @@ def test_full_batch_elementwise(B, name):
         A = M.astype(np.float32).astype(np.float64) + w.prox_lambda * tau * R0[0].astype(np.float64)
         say(f"  {name}: update iters={ust[0]['iters']} ms={ust[0]['ms']:.3f} device orth={ust[0]['orth_err']:.2e}")
         polar_properties(R[0], A, f"{name} polar")
+        # the next batch from the LEARNED rotation: the GPU's updated R becomes the oracle's state
+        oc.reset_stats()
+        oc.R[:] = R
+        step_and_compare(cal, oc, B, I.batch(w, 1), w, f"{name} batch 1 (learned rotation)")
     finally:
         cal.close()
 
 
-def test_c5_sampled(B):
+def test_c5_full_batch(B):
     w = I.WORKLOADS["c5"]
     T, d = w.tokens_per_batch, w.d
     say("  c5: drawing R0 (8192 x 8192 QR) and the batch ...")
     R0 = I.initial_rotation(w)
     X = I.batch(w, 0)
+    oc = O.OracleCalibrator(d, 1, w.dtype, R0, w.prox_lambda)
     cal = B.Calibrator(d, 1, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda)
     try:
-        Xd = B.to_device(X, w.dtype)
-        cal.step_batch(Xd)
-        _, Mg, _ = cal.get_state(want_R=False)
-        Sg, nrm = cal.last_corners(T)
-        st = cal.batch_stats()[0]
-        rows = np.random.Generator(np.random.Philox(key=55)).choice(T, size=96, replace=False)
-        oc = O.OracleCalibrator(d, 1, w.dtype, R0, w.prox_lambda)
-        say("  c5: oracle on 96 sampled token rows ...")
-        Y, S = oc.step_batch(np.ascontiguousarray(X[rows]), True, True)
-        big = np.abs(Y) > 1e-3 * np.linalg.norm(Y, axis=1, keepdims=True)
-        mism = (Sg[rows] != S) & big
-        say(f"  c5: sampled rows: sign mismatches {mism.sum()} of {big.sum()} significant")
-        assert mism.sum() <= 1e-4 * big.sum()
-        assert np.allclose(nrm[0][rows], np.linalg.norm(X[rows].astype(np.float64), axis=1), rtol=1e-5)
-        # l1 term of the sampled rows, recomputed from the oracle's y, against the GPU's whole-batch L by scaling
-        # is not exact; the exact tie is the identity <R_op, M> = L / sqrt(d) on the GPU's own M and L:
-        Rop = O.round_operand(R0, w.dtype)[0].astype(np.float64)
-        lhs = float((Rop * Mg[0].astype(np.float64)).sum())
-        rhs = st["l1"] / math.sqrt(d)
-        say(f"  c5: <R_op, M> = {lhs:.6e}   L/sqrt(d) = {rhs:.6e}")
-        assert abs(lhs - rhs) <= 1e-3 * abs(rhs)
-        assert st["rows"] == T and st["skipped"] == 0
-        # the sampled rows' contribution to M equals the oracle's M of those rows: check it through
-        # M's action on a probe, M^T x_hat_i summed = sum_i c_i ||x_hat_i||^2 ... (linear in tokens):
-        # GPU run on the sampled rows alone must reproduce the oracle's M of the sample
-        cal2 = B.Calibrator(d, 1, w.dtype, R0, max_tokens=128, prox_lambda=w.prox_lambda)
-        try:
-            cal2.step_batch(B.to_device(np.ascontiguousarray(X[rows]), w.dtype))
-            _, M2, _ = cal2.get_state(want_R=False)
-            relM = np.linalg.norm(M2[0] - oc.M[0]) / np.linalg.norm(oc.M[0])
-            say(f"  c5: M of the 96 sampled rows, GPU vs oracle: rel. Frobenius {relM:.2e}")
-            assert relM <= 1e-3
-        finally:
-            cal2.close()
-        # the scores and the emitted fake-quantised rows on the whole batch, against the oracle on the sampled rows
+        say(f"  c5: oracle step_batch on the whole {T} x {d} batch ...")
+        Xd, Mg = step_and_compare(cal, oc, B, X, w, "c5 batch 0 (Haar R0)")
+        # a batch with massive-activation rows (x1000 on two channels, as workload c3 has them): after normalisation the
+        # other entries of such a row are tiny; the accumulate operand must still carry them
+        say("  c5: oracle quant_error on the whole batch ...")
+        so, eo, _, _ = oc.quant_error(X, 4)
+        sg, eg = cal.quant_error(Xd, 4)
+        say(f"  c5: int4 SSE gpu={sg:.6e} oracle={so:.6e}  energy gpu={eg:.6e} oracle={eo:.6e}")
+        assert abs(sg - so) <= 1e-3 * so and abs(eg - eo) <= 1e-3 * eo
+        # zero-point score, emitted rows and diagnostics on the whole batch against the oracle on sampled rows
+        rows = np.sort(np.random.Generator(np.random.Philox(key=55)).choice(T, size=96, replace=False))
         Xs = np.ascontiguousarray(X[rows])
         Qg = cal.rotate_quant(Xd, 4, True, 0.9).float().cpu().numpy()[rows]
         Qo = oc.fake_quant(Xs, 4, True, 0.9)
@@ -171,18 +166,68 @@ def test_c5_sampled(B):
         pr_g, rho_g = cal.row_diagnostics(Xd)
         pr_o, rho_o = oc.row_diagnostics(Xs)
         assert np.allclose(pr_g[rows], pr_o, rtol=1e-3, atol=1e-7) and np.allclose(rho_g[rows], rho_o, rtol=1e-3, atol=1e-7)
-        # update at d = 8192 from the GPU's M, checked by properties
+        # update at d = 8192 from the oracle's M, checked by the polar factor's defining properties (objective included)
+        M = oc.M[0]
+        cal.set_state(M=M.astype(np.float32))
         _, ust = cal.update_rotation()
         R, _, _ = cal.get_state(want_M=False)
-        tau = np.linalg.norm(Mg[0].astype(np.float64)) / math.sqrt(d)
-        A = Mg[0].astype(np.float64) + w.prox_lambda * tau * R0[0].astype(np.float64)
+        tau = np.linalg.norm(M) / math.sqrt(d)
+        A = M.astype(np.float32).astype(np.float64) + w.prox_lambda * tau * R0[0].astype(np.float64)
         say(f"  c5: update iters={ust[0]['iters']} ms={ust[0]['ms']:.3f} device orth={ust[0]['orth_err']:.2e}")
+        polar_properties(R[0], A, "c5 polar")
+        # the next batch from the learned rotation
+        oc.reset_stats()
+        oc.R[:] = R
+        step_and_compare(cal, oc, B, I.batch(w, 1), w, "c5 batch 1 (learned rotation)")
+    finally:
+        cal.close()
+
+
+def test_massive_rows_at_d8192(B):
+    """Rows with massive activations (x1000 on two channels) at d = 8192: after normalisation every other entry of such
+    a row is below 1e-4; the accumulate operand (x^ in fp16) must not lose them.  A short batch, the oracle on all of it."""
+    w5 = I.WORKLOADS["c5"]
+    w = I.Workload("c5_massive", w5.d, 1, "bf16", 192, 1, w5.sigma, w5.n_outliers, w5.outlier_lo, w5.outlier_hi, True, 0.25,
+                   w5.prox_lambda, 2005)
+    X = I.batch(w, 0)
+    R0 = I.hadamard_rotation(w.d, 1, seed=3)          # cheap to draw at this width, and orthogonal exactly
+    oc = O.OracleCalibrator(w.d, 1, "bf16", R0, w.prox_lambda)
+    cal = B.Calibrator(w.d, 1, "bf16", R0, max_tokens=192, prox_lambda=w.prox_lambda)
+    try:
+        step_and_compare(cal, oc, B, X, w, "massive rows d=8192")
+    finally:
+        cal.close()
+
+
+@pytest.mark.parametrize("d,lam", [(4096, 0.1), (4096, 0.0), (8192, 0.1)])
+def test_planted_polar_at_bench_size(B, d, lam):
+    """A = Q P with P symmetric positive definite of prescribed spectrum (condition 1e4): polar(A) = Q and the optimum of
+    <R, A> is the sum of the prescribed singular values -- a closed form at sizes no Jacobi SVD reaches.  With the
+    proximal term (the benchmark's configuration, lambda = 0.1) the previous rotation is Q itself, so that
+    A + lambda tau Q = Q (P + lambda tau I) keeps Q as its polar factor and the optimum is sum(sigma) + lambda tau d."""
+    say(f"  planted polar d={d} lambda={lam}: drawing Q and P ...")
+    Q = I.random_orthogonal(d, 141)
+    sig = np.logspace(0, -4, d)
+    Wo = I.hadamard_rotation(d, 1, seed=17)[0].astype(np.float64)      # P's eigenvectors: orthogonal exactly, cheap to draw
+    P = (Wo * sig[None, :]) @ Wo.T
+    P = 0.5 * (P + P.T)
+    A = (Q @ P).astype(np.float32)
+    cal = B.Calibrator(d, 1, "bf16", Q.astype(np.float32), max_tokens=64, prox_lambda=lam)
+    try:
+        cal.set_state(M=A)
+        rc, st = cal.update_rotation()
+        R, _, _ = cal.get_state(want_M=False)
         R64 = R[0].astype(np.float64)
         orth = np.linalg.norm(R64.T @ R64 - np.eye(d))
-        Sm = R64.T @ A
-        asym = np.linalg.norm(Sm - Sm.T) / np.linalg.norm(Sm)
-        say(f"  c5 polar: orth={orth:.2e} asym(R^T A)={asym:.2e} <R,A>={np.trace(Sm):.6e}")
+        A64 = A.astype(np.float64)
+        tau = np.linalg.norm(A64) / math.sqrt(d)
+        Aprox = A64 + lam * tau * Q.astype(np.float32).astype(np.float64)
+        got = float((R64 * Aprox).sum())
+        best = float(sig.sum() + lam * tau * d)
+        say(f"  planted polar d={d} lambda={lam}: iters={st[0]['iters']} ms={st[0]['ms']:.3f} orth={orth:.2e} "
+            f"<R,A>={got:.6e} optimum={best:.6e} max|R-Q|={np.abs(R64 - Q).max():.2e}")
         assert orth <= 1e-4
-        assert asym <= 5e-2     # symmetric up to the small-singular-value directions the fast mode leaves loose
+        assert abs(got - best) <= 1e-3 * best
+        assert abs(st[0]["inner"] - float((R64 * A64).sum())) <= 1e-4 * abs(st[0]["inner"])
     finally:
         cal.close()

@@ -45,7 +45,8 @@ def compare_step(B, cal, oc, X, w, tag):
     Xd = B.to_device(X, w.dtype)
     cal.set_taps(True)      # the fused per-head step keeps its corner signs only on request
     cal.step_batch(Xd)
-    _, Mg, _ = cal.get_state(want_R=False)
+    _, Mg, n_rows = cal.get_state(want_R=False)
+    assert np.array_equal(n_rows, oc.n)      # rows that entered M since the last update, per head
     Sg, nrm = cal.last_corners(X.shape[0])
     dh = w.dh
     for h in range(w.heads):
@@ -167,8 +168,8 @@ def compare_quant(B, cal, oc, X, w, tag):
         assert abs(sse_rows - sg) <= (2e-2 if w.dtype == "bf16" else 1e-4) * sg + 1e-30, (tag, sse_rows, sg)
 
 
-def run_stream(B, w, n_batches, check_R, tokens=None, **cal_kwargs):
-    R0 = I.initial_rotation(w)
+def run_stream(B, w, n_batches, check_R, tokens=None, R0=None, **cal_kwargs):
+    R0 = I.initial_rotation(w) if R0 is None else R0
     T = w.tokens_per_batch if tokens is None else tokens
     oc = O.OracleCalibrator(w.d, w.heads, w.dtype, R0, w.prox_lambda)
     cal = B.Calibrator(w.d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda, **cal_kwargs)
@@ -213,6 +214,52 @@ def test_polar_options(B, precision, verify):
     w = I.small_workload(384, 300, n_batches=2, seed=911, prox_lambda=0.1, massive_frac=0.01)
     # measured: 2e-3 / 4e-6 / 2e-7 -- rounding of the main phase, amplified by 1/sigma on the weak directions
     run_stream(B, w, 2, check_R={0: 2e-2, 1: 5e-5, 2: 5e-6}[precision], polar_precision=precision, polar_verify=verify)
+
+
+@pytest.mark.parametrize("name", ["c1", "c4"])
+def test_default_polar_precision_where_it_matters(B, name):
+    """What the default update (single bf16 operand planes in the main phase) costs where lambda = 0 makes M's weak
+    directions count (workloads c1 and c4): from the same M, the update in the default mode and in the fp32-equivalent
+    mode, then the NEXT batch under each rotation -- Eq. 1, the corner signs and the int4 error, which is what the
+    rotation is for -- against the oracle's exact update.  R itself may differ on the weak directions; the objective
+    may not (tolerance 1e-3)."""
+    w = I.WORKLOADS[name]
+    T = w.tokens_per_batch
+    R0 = I.initial_rotation(w)
+    X0, X1 = I.batch(w, 0), I.batch(w, 1)
+    oc = O.OracleCalibrator(w.d, w.heads, w.dtype, R0, w.prox_lambda)
+    oc.step_batch(X0)
+    M = oc.M.astype(np.float32)
+    oc.update_rotation()
+    R_o = oc.R.copy()
+    Y1, S1 = oc.step_batch(X1, True, True)
+    obj_o = oc.objective().sum()
+    so, eo, _, _ = oc.quant_error(X1, 4)
+    big = np.abs(Y1).reshape(T, w.heads, w.dh) > 1e-3 * np.linalg.norm(Y1.reshape(T, w.heads, w.dh), axis=2, keepdims=True)
+    big = big.reshape(T, w.d)
+    X1d = B.to_device(X1, w.dtype)
+    for precision in (0, 2):
+        cal = B.Calibrator(w.d, w.heads, w.dtype, R0, max_tokens=T, prox_lambda=w.prox_lambda, polar_precision=precision)
+        try:
+            cal.set_taps(True)
+            cal.set_state(M=M)
+            _, st = cal.update_rotation()
+            R, _, _ = cal.get_state(want_M=False)
+            cal.step_batch(X1d)
+            obj_g = cal.objective().sum()
+            Sg, _ = cal.last_corners(T)
+            sg, eg = cal.quant_error(X1d, 4)
+            flips = ((Sg != S1) & big).sum() / big.sum()
+            say(f"  {name} polar_precision={precision}: update {st[0]['ms']:.3f} ms ({st[0]['iters']} iters), max|R - R_oracle| = "
+                f"{np.abs(R - R_o).max():.2e}; next batch: objective {obj_g:.6e} vs oracle {obj_o:.6e} "
+                f"(rel {abs(obj_g - obj_o) / obj_o:.2e}), corner signs differing {flips:.2e}, int4 rel.err "
+                f"{sg / eg:.6e} vs {so / eo:.6e}")
+            assert abs(obj_g - obj_o) <= TOL_REL * obj_o
+            assert abs(sg / eg - so / eo) <= (5 if precision == 0 else 1) * TOL_REL * so / eo
+            for h in range(w.heads):
+                assert np.linalg.norm(R[h].astype(np.float64).T @ R[h] - np.eye(w.dh)) <= TOL_ORTH
+        finally:
+            cal.close()
 
 
 def test_polar_precision_improves_R(B):
@@ -279,9 +326,95 @@ def test_fused_head_step_shapes(B, heads, T):
         cal.close()
 
 
-def test_c4_heads_reduced_tokens(B):
-    """Config c4's shape (32 heads x 128) on a 512-token batch."""
-    run_stream(B, I.WORKLOADS["c4"], 1, check_R=False, tokens=512)
+def test_c4_stream_own_recipe(B):
+    """Config c4 on its own recipe and at its own size: 32 heads x 128, 2048 tokens per batch, lambda = 0; two
+    teacher-forced batches, each with the batched per-head update (fused step kernel + one-launch polar main phase)."""
+    run_stream(B, I.WORKLOADS["c4"], 2, check_R=False)
+
+
+@pytest.mark.parametrize("d,heads,dtype", [(256, 1, "bf16"), (512, 4, "bf16"), (128, 1, "f32")])
+def test_stream_from_hadamard_rotation(B, d, heads, dtype):
+    """The stream started from a randomised Hadamard rotation (App. C: the fixed rotation the learned ones are compared
+    with) instead of a Haar one.  Its entries +-1/sqrt(dh) are exact in bf16, so every |y| of a row is a sum of the same
+    magnitudes with different signs: many near-cancellations, the hard case for the corner signs."""
+    w = I.small_workload(d, 300, n_batches=2, heads=heads, dtype=dtype, seed=777 + d, prox_lambda=0.1, massive_frac=0.01)
+    run_stream(B, w, 2, check_R=True, R0=I.hadamard_rotation(d, heads, seed=5))
+
+
+def test_fold_rotation_into_weight_matrix_in_chunks(B):
+    """Folding the learned rotation into a weight matrix (App. A: W' = W R, the rows of W as X) whose row count exceeds
+    max_tokens: the caller walks over the matrix in chunks of at most max_tokens rows, into slices of one output."""
+    import torch
+    d, rows, chunk = 384, 1000, 128
+    w = I.small_workload(d, rows, n_batches=1, seed=31, student_t=False, n_outliers=0)
+    Wm = I.batch(w, 0)                       # stands in for a weight matrix with `rows` output features
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(d, 1, "bf16", R0)
+    cal = B.Calibrator(d, 1, "bf16", R0, max_tokens=chunk)
+    try:
+        Wd = B.to_device(Wm, "bf16")
+        out = torch.zeros((rows, d), dtype=Wd.dtype, device=Wd.device)
+        with pytest.raises(B.ConqurError) as e:
+            cal.rotate(Wd, out)                                   # the whole matrix at once is more than max_tokens
+        assert e.value.status == B.EINVAL
+        for r0 in range(0, rows, chunk):
+            cal.rotate(Wd[r0:r0 + chunk], out[r0:r0 + chunk])     # the last chunk is ragged (1000 = 7 * 128 + 104)
+        torch.cuda.synchronize()
+        Yg = out.float().cpu().numpy()
+        Yo = oc.rotate(Wm)
+        assert np.all(np.abs(Yg - Yo) <= 2.0 ** -7 * np.abs(Yo) + 1e-6 * np.abs(Yo).max())
+        assert np.mean(Yg == Yo) > 0.98
+    finally:
+        cal.close()
+
+
+def test_offline_iid_driver(B):
+    """The offline variant of Sec. 4.4 (activations stored first, then sampled i.i.d. for every update, with the same
+    number of rows per update and of updates as the online loop) through the package's driver: same kernels, another
+    order of rows.  Teacher-forced against the oracle stepping the same sampled rows."""
+    from paper_2605_10793_amd import drivers
+    w = I.small_workload(256, 400, n_batches=3, seed=515, prox_lambda=0.1, massive_frac=0.01)
+    pool = np.concatenate([I.batch(w, b) for b in range(3)])          # the stored activations
+    pool_dev = B.to_device(pool, w.dtype)
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(w.d, 1, w.dtype, R0, w.prox_lambda)
+    cal = B.Calibrator(w.d, 1, w.dtype, R0, max_tokens=400, prox_lambda=w.prox_lambda)
+    seen = []
+
+    def on_batch(u, idx):
+        X = pool[idx]
+        Y, S = oc.step_batch(X, True, True)
+        _, Mg, _ = cal.get_state(want_R=False)
+        relM = np.linalg.norm(Mg[0] - oc.M[0]) / np.linalg.norm(oc.M[0])
+        Sg, _ = cal.last_corners(len(idx))
+        big = np.abs(Y) > 1e-3 * np.linalg.norm(Y, axis=1, keepdims=True)
+        st = cal.batch_stats()[0]
+        say(f"  offline update {u}: relM={relM:.2e} sign mismatches {((Sg != S) & big).sum()} L gpu={st['l1']:.6e} oracle={oc.L[0]:.6e}")
+        assert relM <= TOL_M and ((Sg != S) & big).sum() <= TOL_SIGN * big.sum()
+        assert st["rows"] == oc.n[0] and abs(st["l1"] - oc.L[0]) <= TOL_REL * oc.L[0]
+        cal.set_state(M=oc.M.astype(np.float32))                      # same M on both sides: R itself is compared
+
+    def on_update(u, st):
+        oc.update_rotation()
+        R, _, _ = cal.get_state(want_M=False)
+        dR = np.abs(R[0] - oc.R[0]).max()
+        R64 = R[0].astype(np.float64)
+        assert np.linalg.norm(R64.T @ R64 - np.eye(w.d)) <= TOL_ORTH and dR <= 2e-2, (u, dR)
+        cal.set_state(R=oc.R)                                          # teacher forcing for the next update
+        seen.append(u)
+
+    try:
+        idx_all = drivers.offline_iid(cal, pool_dev, rows_per_update=400, n_updates=3, seed=99, on_batch=on_batch,
+                                      on_update=on_update)
+        assert seen == [0, 1, 2] and len(idx_all) == 3
+        assert len(np.unique(idx_all[0])) < 400                        # drawn with replacement from the 1200 stored rows
+        assert not np.array_equal(idx_all[0], idx_all[1])
+        # the online driver over the same three batches: the loop the benchmark times
+        drivers.online(cal, [pool_dev[b * 400:(b + 1) * 400] for b in range(3)])
+        R, _, _ = cal.get_state(want_M=False)
+        assert np.linalg.norm(R[0].astype(np.float64).T @ R[0] - np.eye(w.d)) <= TOL_ORTH
+    finally:
+        cal.close()
 
 
 def test_free_running_streams(B):

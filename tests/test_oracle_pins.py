@@ -655,9 +655,19 @@ def test_fake_quant_levels_error_bound_and_rotation(dtype):
         slack = np.abs(Q).max(1, keepdims=True) * ulp + 1e-6 * span[:, None]
         assert (err <= 0.5 * span[:, None] + slack).mean() > (0.97 if zp else 0.999)
         assert (err <= (1.0 if zp else 0.5) * span[:, None] + slack).all()
+        sse, _, rows_sse, _ = (oc.quant_error_zp(X, bits, 1.0, want_rows=True) if zp else
+                               oc.quant_error(X, bits, want_rows=True))
         if dtype == "f32":
-            sse = (oc.quant_error_zp(X, bits, 1.0) if zp else oc.quant_error(X, bits))[0]
             assert np.isclose((err ** 2).sum(), sse, rtol=1e-6)
+        else:
+            # bf16: the emitted level is the error functions' level q rounded once into bf16, |Q - q| <= 2^-9 |q|; per
+            # row, by the triangle inequality in l2, | ||Q - y|| - ||q - y|| | <= ||Q - q|| <= 2^-9 ||Q|| (1 + 2^-8)
+            emit = np.sqrt((err ** 2).sum(1))
+            lvl = 2.0 ** -9 * (1 + 2.0 ** -8) * np.sqrt((Q ** 2).sum(1))
+            assert np.all(np.abs(emit - np.sqrt(rows_sse)) <= lvl + 1e-12), (zp, bits)
+            # and the rounding is really there and really small: the totals agree to a few level roundings, not exactly
+            assert abs((err ** 2).sum() - sse) <= 2 * np.sqrt(sse) * np.sqrt((lvl ** 2).sum()) + (lvl ** 2).sum()
+            assert np.array_equal(Q, torch.from_numpy(Q).to(torch.bfloat16).double().numpy())      # values are bf16
     # identity rotation: quantising the rotated rows is quantising the rows; block structure: heads do not mix
     oi = O.OracleCalibrator(d, heads, dtype, np.stack([np.eye(32, dtype=np.float32)] * heads))
     Xs = X.copy(); Xs[:, 32:] = 0.0
