@@ -269,7 +269,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   A(dev_alloc(ctx, &ctx->PW, 3 * blk));
   A(dev_alloc(ctx, &ctx->PW2, 3 * blk));
   A(dev_alloc(ctx, &ctx->resid, (size_t)kResidSlots * ctx->heads));
-  ctx->resid_parts = gemm_num_partials((int)dh, (int)dh, ctx->heads);
+  ctx->resid_parts = gemm_num_partials((int)dh, (int)dh, ctx->heads, 1);   // every launch that leaves residual partials is a symmetric one
   A(dev_alloc(ctx, &ctx->resid_part, (size_t)ctx->resid_parts * ctx->heads));
   ctx->head_fused = ctx->dh == 128 && !ctx->f32;
   if (ctx->head_fused) {

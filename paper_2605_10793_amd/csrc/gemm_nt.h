@@ -78,8 +78,9 @@ hipError_t launch_gemm_nt(const GemmArgs& args, GemmEpilogue epi, int batch, hip
 // Number of workgroups launch_gemm_nt uses for an M x N problem with `batch` entries (size of the clock probe / 4).
 int gemm_num_workgroups(int M, int N, int batch);
 
-// Per-batch-entry count of the partial sums the EPI_GRAMW epilogue writes for an M x N problem.
-int gemm_num_partials(int M, int N, int batch);
+// Per-batch-entry count of the partial sums the EPI_GRAMW / EPI_FRO2 epilogues write for an M x N problem launched
+// with the given `symmetric` flag (the flag can select another tile).
+int gemm_num_partials(int M, int N, int batch, int symmetric);
 
 
 }  // namespace conqur

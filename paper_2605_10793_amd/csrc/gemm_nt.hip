@@ -582,6 +582,26 @@ int pick_tile(int M, int N, int batch) {
   return best;
 }
 
+constexpr int kSymMinTiles = 8;   // tiles per side from which the mirrored form is used
+
+// Tile for a symmetric product (only the t (t + 1) / 2 tiles on and above the diagonal run): the square tile with the
+// least rounds x tile area / efficiency, or -1 if no square tile gives at least kSymMinTiles per side.  Counting the
+// tiles that really run matters: at 4096 the 256 x 256 tile leaves 136 workgroups on 256 compute units, the 192 x 192
+// tile 253 (measured 80 against 96 us for a Gram matrix); at 8192 it is 946 tiles in 4 rounds against 528 in 3.
+int pick_tile_sym(int M, int batch) {
+  int best = -1;
+  double best_cost = 1e300;
+  for (int t = 0; t < kNumTiles; ++t) {
+    if (kTiles[t].bm != kTiles[t].bn) continue;
+    const int64_t side = (M + kTiles[t].bm - 1) / kTiles[t].bm;
+    if (side < kSymMinTiles) continue;
+    const int64_t rounds = (side * (side + 1) / 2 * batch + 255) / 256;
+    const double cost = (double)rounds * kTiles[t].bm * kTiles[t].bn / kTiles[t].eff;
+    if (cost < best_cost) { best_cost = cost; best = t; }
+  }
+  return best;
+}
+
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool F16, bool SYM = false>
 hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
@@ -598,21 +618,16 @@ hipError_t launch_one(const GemmArgs& a, int batch, hipStream_t stream) {
   return hipGetLastError();
 }
 
-constexpr int kSymMinTiles = 8;   // tiles per side from which the mirrored form is used
-
 template <int EPI, bool F16 = false>
 hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
   if constexpr (EPI == EPI_GRAMW || EPI == EPI_SQUARE || EPI == EPI_FRO2) {
-    if (a.symmetric) {   // tiles on and above the diagonal only, where the chosen tile is square and there are enough
-      const int t = pick_tile(a.M, a.N, batch);
-      if (kTiles[t].bm == kTiles[t].bn && (a.M + kTiles[t].bm - 1) / kTiles[t].bm >= kSymMinTiles) {
-        switch (t) {
-          case 0: return launch_one<256, 256, 2, 4, 2, EPI, F16, true>(a, batch, stream);
-          case 2: return launch_one<128, 128, 2, 2, 3, EPI, F16, true>(a, batch, stream);
-          case 4: return launch_one<192, 192, 3, 2, 3, EPI, F16, true>(a, batch, stream);
-          case 3: return launch_one<64, 64, 2, 2, 3, EPI, F16, true>(a, batch, stream);
-          default: break;
-        }
+    if (a.symmetric) {   // tiles on and above the diagonal only, where a square tile gives enough of them per side
+      switch (pick_tile_sym(a.M, batch)) {
+        case 0: return launch_one<256, 256, 2, 4, 2, EPI, F16, true>(a, batch, stream);
+        case 2: return launch_one<128, 128, 2, 2, 3, EPI, F16, true>(a, batch, stream);
+        case 4: return launch_one<192, 192, 3, 2, 3, EPI, F16, true>(a, batch, stream);
+        case 3: return launch_one<64, 64, 2, 2, 3, EPI, F16, true>(a, batch, stream);
+        default: break;
       }
     }
   }
@@ -629,9 +644,14 @@ hipError_t launch_epi(const GemmArgs& a, int batch, hipStream_t stream) {
 
 }  // namespace
 
-int gemm_num_partials(int M, int N, int batch) {
-  const Tile& t = kTiles[pick_tile(M, N, batch)];
-  return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * t.wgm * t.wgn;
+int gemm_num_partials(int M, int N, int batch, int symmetric) {
+  int t = pick_tile(M, N, batch);
+  if (symmetric && M == N) {
+    const int ts = pick_tile_sym(M, batch);
+    if (ts >= 0) t = ts;
+  }
+  const Tile& u = kTiles[t];
+  return ((M + u.bm - 1) / u.bm) * ((N + u.bn - 1) / u.bn) * u.wgm * u.wgn;
 }
 
 int gemm_num_workgroups(int M, int N, int batch) {
