@@ -203,6 +203,19 @@ conqur_status conqur_rotate_quant(conqur_ctx* ctx, const void* X_dev, uint64_t T
                                   uint32_t zero_point, float clip_ratio, void* Yq_dev, uint64_t yq_row_stride_elems);
 
 /*
+ * Quantisation-aware calibration (Sec. 3.4, second paragraph: during calibration the input of every
+ * linear layer is quantised after the current rotation has been applied, so that later sites see
+ * the activations inference will give them): conqur_step_batch and conqur_rotate_quant of the same
+ * batch in ONE call and from ONE rotation of X.  The site's statistics are accumulated exactly as
+ * conqur_step_batch does, and Yq_dev receives Q(X R_op) exactly as conqur_rotate_quant writes it --
+ * the quantised input of the layer behind the site.  Arguments and errors as for those two calls.
+ * (Heads of width 128 with bf16 activations rotate twice internally: their fused step keeps the
+ * rotated rows on the compute unit.)  Asynchronous on the context's stream.
+ */
+conqur_status conqur_step_batch_quant(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems, uint32_t bits,
+                                      uint32_t zero_point, float clip_ratio, void* Yq_dev, uint64_t yq_row_stride_elems);
+
+/*
  * Per-row diagnostics of the rotated activations: Y = X R_op per head, stored in
  * act_dtype, then per token over the whole row of width d
  *   pr  = ||y||_2^4 / (d ||y||_4^4)   normalised participation ratio (Sec. 4.2), in [1/d, 1]

@@ -21,7 +21,7 @@ STATUS_NAMES = ["OK", "EINVAL", "ESTATE", "ENOMEM", "EHIP", "ENOCONV", "ENONFINI
 F32, BF16 = 0, 1
 
 EXPORTS = [
-    "conqur_init", "conqur_step_batch", "conqur_step_batch_heads", "conqur_get_batch_stats", "conqur_update_rotation",
+    "conqur_init", "conqur_step_batch", "conqur_step_batch_heads", "conqur_step_batch_quant", "conqur_get_batch_stats", "conqur_update_rotation",
     "conqur_quant_error", "conqur_quant_error_zp", "conqur_rotate", "conqur_rotate_quant", "conqur_row_diagnostics", "conqur_get_state", "conqur_set_state", "conqur_get_last_corners",
     "conqur_score_rows_static", "conqur_set_taps", "conqur_set_timing", "conqur_get_timing", "conqur_get_clock_probe", "conqur_last_error", "conqur_destroy", "conqur_version",
 ]
@@ -68,6 +68,8 @@ def load() -> ctypes.CDLL:
         L.conqur_step_batch.argtypes = [vp, vp, u64, u64]
         L.conqur_step_batch_heads.restype = i32
         L.conqur_step_batch_heads.argtypes = [vp, vp, u64, u64, ctypes.c_uint32, ctypes.c_uint32]
+        L.conqur_step_batch_quant.restype = i32
+        L.conqur_step_batch_quant.argtypes = [vp, vp, u64, u64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_float, vp, u64]
         L.conqur_get_batch_stats.restype = i32
         L.conqur_get_batch_stats.argtypes = [vp, vp]
         L.conqur_update_rotation.restype = i32
@@ -168,6 +170,18 @@ class Calibrator:
         if X.dim() != 2 or X.stride(1) != 1 or not X.is_cuda or X.dtype != want or X.shape[1] < nheads * self.dh:
             raise ValueError(f"X must be a 2-D {want} device tensor with >= nheads * dh columns and unit column stride")
         self._check(self._lib.conqur_step_batch_heads(self._h, X.data_ptr(), X.shape[0], X.stride(0), head0, nheads))
+
+    def step_batch_quant(self, X, bits: int = 4, zero_point: bool = True, clip_ratio: float = 1.0, Yq=None):
+        """step_batch(X) and Yq = Q(X R_op) from one rotation of the batch (quantisation-aware calibration); asynchronous."""
+        import torch
+        p, T, stride = self._x(X)
+        if Yq is None:
+            Yq = torch.empty((T, self.d), dtype=X.dtype, device=X.device)
+        if Yq.dtype != X.dtype or Yq.dim() != 2 or Yq.shape[0] != T or Yq.shape[1] < self.d or Yq.stride(1) != 1:
+            raise ValueError("Yq must be a [T, >= d] tensor of X's dtype with unit column stride")
+        self._check(self._lib.conqur_step_batch_quant(self._h, p, T, stride, bits, 1 if zero_point else 0,
+                                                      ctypes.c_float(clip_ratio), ctypes.c_void_p(Yq.data_ptr()), Yq.stride(0)))
+        return Yq
 
     def batch_stats(self) -> List[dict]:
         arr = (BatchStats * self.heads)()

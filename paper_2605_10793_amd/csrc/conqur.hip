@@ -414,15 +414,11 @@ conqur_status conqur_step_batch_heads(conqur_ctx* ctx, const void* X, uint64_t T
   return step_fused(ctx, X, (int64_t)T64, (int64_t)stride64, (int)head0, (int)nheads);
 }
 
-conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64) {
-  conqur_status st = check_x(ctx, X, T64, stride64);
-  if (st != CONQUR_OK) return st;
-  HIP_TRY(hipSetDevice(ctx->cfg.device));
-  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+// The statistics step of the general path (any head width, both activation dtypes).  keep_y: the rotate GEMM also
+// stores the rotated rows Y = X R_op into ctx->Y (activation dtype), for a quantiser that follows in the same call.
+static conqur_status step_general(conqur_ctx* ctx, const void* X, int64_t T, int64_t stride, bool keep_y) {
   const int64_t Tk = round_up(T, 64);
   hipStream_t s = ctx->stream;
-  StageTimer whole(ctx, ST_STEP, 1);   // ends when the function returns
-  if (ctx->head_fused) return step_fused(ctx, X, T, stride, 0, ctx->heads);
   ctx->last_signs_valid = true;
   {
     StageTimer tm(ctx, ST_PREP);
@@ -442,7 +438,8 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
     const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
     ctx->clk_wg[0] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
     g.clk = ctx->clk_wg[0] ? ctx->clk[0] : nullptr;
-    HIP_TRY(launch_gemm_nt(g, EPI_SIGN, ctx->heads, s));
+    if (keep_y) { g.Yact = ctx->Y; g.ldy = ctx->d; g.batchY = ctx->dh; g.c_is_f32 = ctx->f32; }
+    HIP_TRY(launch_gemm_nt(g, keep_y ? EPI_SIGN_ACT : EPI_SIGN, ctx->heads, s));
   }
   {
     StageTimer tm(ctx, ST_ACCUM);
@@ -468,6 +465,50 @@ conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, ui
   ctx->m_empty = false;
   ctx->have_rows = true;
   ctx->last_T = T;
+  return CONQUR_OK;
+}
+
+conqur_status conqur_step_batch(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  StageTimer whole(ctx, ST_STEP, 1);   // ends when the function returns
+  if (ctx->head_fused) return step_fused(ctx, X, (int64_t)T64, (int64_t)stride64, 0, ctx->heads);
+  return step_general(ctx, X, (int64_t)T64, (int64_t)stride64, false);
+}
+
+conqur_status conqur_step_batch_quant(conqur_ctx* ctx, const void* X, uint64_t T64, uint64_t stride64, uint32_t bits,
+                                      uint32_t zero_point, float clip_ratio, void* Yq, uint64_t yq_stride64) {
+  conqur_status st = check_x(ctx, X, T64, stride64);
+  if (st != CONQUR_OK) return st;
+  if (bits < 2 || bits > 8) return fail(ctx, CONQUR_EINVAL, "bits must be in [2, 8]");
+  if (zero_point > 1) return fail(ctx, CONQUR_EINVAL, "zero_point must be 0 or 1");
+  if (zero_point && (!(clip_ratio > 0.0f) || clip_ratio > 1.0f)) return fail(ctx, CONQUR_EINVAL, "clip_ratio must be in (0, 1]");
+  if (!Yq) return fail(ctx, CONQUR_EINVAL, "Yq_dev is NULL");
+  if (yq_stride64 < (uint64_t)ctx->d || yq_stride64 >= (1ull << 40) || (reinterpret_cast<uintptr_t>(Yq) % 16) != 0 ||
+      (yq_stride64 * (ctx->f32 ? 4 : 2)) % 16 != 0)
+    return fail(ctx, CONQUR_EINVAL, "Yq row stride must be >= d and Yq and its rows aligned to 16 bytes");
+  HIP_TRY(hipSetDevice(ctx->cfg.device));
+  const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
+  hipStream_t s = ctx->stream;
+  {
+    StageTimer whole(ctx, ST_STEP, 1);
+    if (ctx->head_fused) {
+      // heads of width 128: the fused step kernel keeps Y on the compute unit; the rows are rotated once more for the quantiser
+      st = step_fused(ctx, X, T, stride, 0, ctx->heads);
+      if (st != CONQUR_OK) return st;
+      GemmArgs g;
+      rotate_args(ctx, X, T, stride, &g);
+      g.C = ctx->Y; g.ldc = ctx->d; g.batchC = ctx->dh; g.c_is_f32 = ctx->f32;
+      HIP_TRY(launch_gemm_nt(g, EPI_ACT, ctx->heads, s));
+    } else {
+      st = step_general(ctx, X, T, stride, true);   // one rotate GEMM: corner signs and Y
+      if (st != CONQUR_OK) return st;
+    }
+  }
+  StageTimer tm(ctx, ST_QERR);
+  HIP_TRY(launch_quant_error(ctx->Y, ctx->f32, T, ctx->d, ctx->d, (int)bits, (int)zero_point, clip_ratio, ctx->row_sse,
+                             ctx->row_en, nullptr, Yq, (int64_t)yq_stride64, s));
   return CONQUR_OK;
 }
 

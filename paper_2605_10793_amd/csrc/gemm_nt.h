@@ -25,6 +25,8 @@ enum GemmEpilogue : int {
                   // np_out natural planes (Pn) and to np_out transposed planes (Pt) -- the hand-over from the
                   // low-precision polar steps to the closing ones, whose Gram matrix is then exact with 1 or 4 plane
                   // products instead of the 6 a 24-bit iterate needs
+  EPI_SIGN_ACT = 8, // EPI_SIGN and EPI_ACT of the same accumulators: St as for EPI_SIGN, and Y[m][n] = acc stored as bf16 or
+                  // fp32 (Yact): one rotation of a batch serves the corner statistics and the quantiser that follows
 };
 
 constexpr int kMaxSegments = 6;
@@ -48,6 +50,8 @@ struct GemmArgs {
   float out_scale;         // EPI_F32: C = out_scale * acc (+ C)
   int64_t st_rows_valid;   // EPI_SIGN: St rows hold this many m entries (padded pitch), multiple of 4
   int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
+  void* Yact;              // EPI_SIGN_ACT: bf16/f32 Y (element type by c_is_f32), pitch ldy, batch offset batchY
+  int64_t ldy, batchY;
   double* resid_part;      // EPI_GRAMW: [batch][gemm_num_partials()] per-wavefront sums of (acc - I)^2, or null.
                            // (No atomics: same-address atomics from all XCDs serialise at the memory side.)
   float coef_i, coef_g;    // EPI_GRAMW

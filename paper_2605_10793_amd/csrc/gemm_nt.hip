@@ -279,7 +279,24 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   //   m = m0 + wm*WM + im*32 + 8*j + 4*half + i,   column n = n0 + wn*WN + in*32 + col.
   const int mw = m0 + wm * WM, nw = n0 + wn * WN;
 
-  if constexpr (EPI == EPI_SIGN) {
+  if constexpr (EPI == EPI_SIGN_ACT) {   // the rotated rows themselves, as EPI_ACT writes them
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = nw + j * 32 + col;
+        if (n >= g.N) continue;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (m >= g.M) continue;
+          const int64_t off = (int64_t)bz * g.batchY + (int64_t)m * g.ldy + n;
+          if (g.c_is_f32) reinterpret_cast<float*>(g.Yact)[off] = acc[i][j][e];
+          else reinterpret_cast<bf16_bits*>(g.Yact)[off] = f32_to_bf16(acc[i][j][e]);
+        }
+      }
+  }
+  if constexpr (EPI == EPI_SIGN || EPI == EPI_SIGN_ACT) {
     // St is the transpose of the accumulator tile.  Storing it straight from the registers gives every lane 8 bytes of
     // a different row (64 cache lines per store instruction); instead each wavefront transposes its WM x WN block
     // through its own slice of the (now idle) stage memory and stores whole 16-byte chunks, 8 or 16 lanes per row.
@@ -671,6 +688,7 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
   if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
+    case EPI_SIGN_ACT: return a.Yact ? launch_epi<EPI_SIGN_ACT>(a, batch, stream) : hipErrorInvalidValue;
     case EPI_ACT: return launch_epi<EPI_ACT>(a, batch, stream);
     case EPI_F32: return a.ab_f16 ? launch_epi<EPI_F32, true>(a, batch, stream) : launch_epi<EPI_F32>(a, batch, stream);
     case EPI_GRAMW: return a.ab_f16 ? launch_epi<EPI_GRAMW, true>(a, batch, stream) : launch_epi<EPI_GRAMW>(a, batch, stream);

@@ -62,17 +62,18 @@ __global__ void __launch_bounds__(256) k_row_norms(const void* __restrict__ X, i
       for (int u = 0; u < 4; ++u) ss += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
     }
   } else {
+    // eight independent 16-byte loads per lane in flight: a head slice of 4096 bf16 is one round trip to memory
     const bf16_bits* x = reinterpret_cast<const bf16_bits*>(X) + i * stride + (int64_t)h * dh;
     const int nc = dh / 8;
-    for (int c0 = lane; c0 < nc; c0 += 256) {
-      uint4 v[4];
+    for (int c0 = lane; c0 < nc; c0 += 512) {
+      uint4 v[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         const int c = c0 + u * 64;
         v[u] = c < nc ? *reinterpret_cast<const uint4*>(x + c * 8) : make_uint4(0u, 0u, 0u, 0u);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         float f[8];
         unpack8(v[u], f);
 #pragma unroll

@@ -368,6 +368,57 @@ def test_fold_rotation_into_weight_matrix_in_chunks(B):
         cal.close()
 
 
+@pytest.mark.parametrize("d,T,heads,dtype", [(320, 333, 1, "bf16"), (256, 200, 2, "bf16"), (128, 257, 1, "f32"), (192, 100, 4, "bf16")])
+def test_quantisation_aware_step(B, d, T, heads, dtype):
+    """conqur_step_batch_quant: the statistics of a batch and its fake-quantised rotated rows from one call (Sec. 3.4:
+    the input of every linear layer is quantised after the current rotation).  Statistics against the oracle's
+    step_batch, rows against the oracle's fake_quant, and both bit-identical to the two separate calls."""
+    import torch
+    w = I.small_workload(d, T, n_batches=1, heads=heads, dtype=dtype, seed=600 + d, massive_frac=0.01)
+    R0 = I.initial_rotation(w)
+    X = I.batch(w, 0)
+    oc = O.OracleCalibrator(d, heads, dtype, R0)
+    Y, S = oc.step_batch(X, True, True)
+    cal = B.Calibrator(d, heads, dtype, R0, max_tokens=T)
+    ref = B.Calibrator(d, heads, dtype, R0, max_tokens=T)
+    try:
+        Xd = B.to_device(X, dtype)
+        cal.set_taps(True)
+        Yq = cal.step_batch_quant(Xd, 4, True, 0.9)
+        torch.cuda.synchronize()
+        _, Mg, n_rows = cal.get_state(want_R=False)
+        Sg, _ = cal.last_corners(T)
+        st = cal.batch_stats()
+        dh = w.dh
+        for h in range(heads):
+            relM = np.linalg.norm(Mg[h] - oc.M[h]) / np.linalg.norm(oc.M[h])
+            Yh = Y[:, h * dh:(h + 1) * dh]
+            big = np.abs(Yh) > 1e-3 * np.linalg.norm(Yh, axis=1, keepdims=True)
+            mism = (Sg[:, h * dh:(h + 1) * dh] != S[:, h * dh:(h + 1) * dh]) & big
+            assert relM <= TOL_M and mism.sum() <= TOL_SIGN * big.sum(), (h, relM, mism.sum())
+            assert st[h]["rows"] == oc.n[h] and abs(st[h]["l1"] - oc.L[h]) <= TOL_REL * oc.L[h]
+        Qg = Yq.float().cpu().numpy().astype(np.float64)
+        Qo = oc.fake_quant(X, 4, True, 0.9).astype(np.float64)
+        Yr = oc.rotate(X).astype(np.float64)
+        step = 0.9 * (Yr.max(1) - Yr.min(1)) / 15
+        ulp = 2.0 ** -8 if dtype == "bf16" else 1e-6
+        diff = np.abs(Qg - Qo)
+        assert np.all(diff <= step[:, None] * (1 + 2.0 ** -6) + 2 * ulp * np.abs(Qo) + 1e-30)
+        assert (diff <= 4 * ulp * (np.abs(Qo) + step[:, None]) + 1e-30).mean() >= (0.997 if dtype == "bf16" else 0.9995)
+        # the two separate calls give the same bits
+        ref.step_batch(Xd)
+        Yq2 = ref.rotate_quant(Xd, 4, True, 0.9)
+        torch.cuda.synchronize()
+        assert torch.equal(Yq, Yq2)
+        assert np.array_equal(ref.get_state(want_R=False)[1], Mg)
+        with pytest.raises(B.ConqurError) as e:
+            cal.step_batch_quant(Xd, 9, True, 0.9)
+        assert e.value.status == B.EINVAL
+    finally:
+        cal.close()
+        ref.close()
+
+
 def test_offline_iid_driver(B):
     """The offline variant of Sec. 4.4 (activations stored first, then sampled i.i.d. for every update, with the same
     number of rows per update and of updates as the online loop) through the package's driver: same kernels, another
