@@ -420,11 +420,16 @@ static conqur_status step_general(conqur_ctx* ctx, const void* X, int64_t T, int
   const int64_t Tk = round_up(T, 64);
   hipStream_t s = ctx->stream;
   ctx->last_signs_valid = true;
+  // bf16 activations: the scaled transposed operand of the accumulate GEMM is produced by the rotate GEMM's epilogue
+  // (every workgroup transposes the block of X under its output block through the LDS staging of the signs), which
+  // saves the transposing launch; fp32 activations (split planes) and the variant that also emits Y keep that launch.
+  const bool xt_in_gemm = !ctx->f32 && !keep_y;
   {
     StageTimer tm(ctx, ST_PREP);
     HIP_TRY(launch_row_norms(X, ctx->f32, T, stride, ctx->heads, ctx->dh, ctx->nrm, ctx->w, ctx->tmax, ctx->nonfinite, s));
-    HIP_TRY(launch_transpose_scale(X, ctx->f32, T, Tk, stride, ctx->d, ctx->dh, ctx->w, ctx->tmax, ctx->Xt, ctx->pitch,
-                                   (int64_t)ctx->d * ctx->pitch, ctx->np, ctx->cnt, s));
+    if (!xt_in_gemm)
+      HIP_TRY(launch_transpose_scale(X, ctx->f32, T, Tk, stride, ctx->d, ctx->dh, ctx->w, ctx->tmax, ctx->Xt, ctx->pitch,
+                                     (int64_t)ctx->d * ctx->pitch, ctx->np, ctx->cnt, s));
     if (ctx->f32)
       HIP_TRY(launch_split_rows(reinterpret_cast<const float*>(X), T, stride, ctx->d, ctx->Xs, ctx->tmax * ctx->d, s));
   }
@@ -439,7 +444,10 @@ static conqur_status step_general(conqur_ctx* ctx, const void* X, int64_t T, int
     ctx->clk_wg[0] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
     g.clk = ctx->clk_wg[0] ? ctx->clk[0] : nullptr;
     if (keep_y) { g.Yact = ctx->Y; g.ldy = ctx->d; g.batchY = ctx->dh; g.c_is_f32 = ctx->f32; }
-    HIP_TRY(launch_gemm_nt(g, keep_y ? EPI_SIGN_ACT : EPI_SIGN, ctx->heads, s));
+    if (xt_in_gemm) {
+      g.xt_w = ctx->w; g.xt_ldw = ctx->tmax; g.Xt = ctx->Xt; g.cnt = ctx->cnt; g.cnt_slots = kCountSlots;
+    }
+    HIP_TRY(launch_gemm_nt(g, keep_y ? EPI_SIGN_ACT : (xt_in_gemm ? EPI_SIGN_XT : EPI_SIGN), ctx->heads, s));
   }
   {
     StageTimer tm(ctx, ST_ACCUM);

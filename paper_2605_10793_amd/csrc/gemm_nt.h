@@ -27,6 +27,11 @@ enum GemmEpilogue : int {
                   // products instead of the 6 a 24-bit iterate needs
   EPI_SIGN_ACT = 8, // EPI_SIGN and EPI_ACT of the same accumulators: St as for EPI_SIGN, and Y[m][n] = acc stored as bf16 or
                   // fp32 (Yact): one rotation of a batch serves the corner statistics and the quantiser that follows
+  EPI_SIGN_XT = 9, // EPI_SIGN, and the accumulate GEMM's other operand on the way (square problems, N == K, bf16 A): every
+                  // wavefront also takes the block of A that lies under its output block (rows = its tokens, columns = its
+                  // output columns read as input channels), scales each row by w, converts to fp16 and stores it
+                  // transposed, Xt[channel][token], through the same LDS staging as the signs; the first tile column
+                  // counts the rows (w != 0 / w == 0) into cnt.  Saves the separate transposing launch.
 };
 
 constexpr int kMaxSegments = 6;
@@ -50,6 +55,11 @@ struct GemmArgs {
   float out_scale;         // EPI_F32: C = out_scale * acc (+ C)
   int64_t st_rows_valid;   // EPI_SIGN: St rows hold this many m entries (padded pitch), multiple of 4
   int sign_f16;            // EPI_SIGN: write +-1 as fp16 instead of bf16
+  const float* xt_w;       // EPI_SIGN_XT: row weights [batch][ldw] (0: the row is skipped and contributes zeros)
+  int64_t xt_ldw;
+  bf16_bits* Xt;           // EPI_SIGN_XT: fp16 [batch][N][ldc] (pitch and batch offset of C), columns m < st_rows_valid written
+  unsigned long long* cnt; // EPI_SIGN_XT: [batch][cnt_slots][2] row counters (entered, skipped); tile row tm adds to slot tm % cnt_slots
+  int cnt_slots;
   void* Yact;              // EPI_SIGN_ACT: bf16/f32 Y (element type by c_is_f32), pitch ldy, batch offset batchY
   int64_t ldy, batchY;
   double* resid_part;      // EPI_GRAMW: [batch][gemm_num_partials()] per-wavefront sums of (acc - I)^2, or null.

@@ -296,7 +296,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         }
       }
   }
-  if constexpr (EPI == EPI_SIGN || EPI == EPI_SIGN_ACT) {
+  if constexpr (EPI == EPI_SIGN || EPI == EPI_SIGN_ACT || EPI == EPI_SIGN_XT) {
     // St is the transpose of the accumulator tile.  Storing it straight from the registers gives every lane 8 bytes of
     // a different row (64 cache lines per store instruction); instead each wavefront transposes its WM x WN block
     // through its own slice of the (now idle) stage memory and stores whole 16-byte chunks, 8 or 16 lanes per row.
@@ -306,6 +306,26 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
     constexpr int CPR = WM / 8;                       // 16-byte chunks per staged row, XOR swizzled by the row
     static_assert(NW * WN * SROW <= NSTAGE * STAGE && (CPR & (CPR - 1)) == 0, "sign staging fits the stage memory");
     unsigned char* stg = smem + wave * (WN * SROW);
+    // EPI_SIGN_XT: the block of A this wavefront transposes below, loaded now so that the sign staging covers the latency
+    constexpr int XT_ITEMS = EPI == EPI_SIGN_XT ? (WM / 2) * (WN / 8) / 64 : 1;
+    [[maybe_unused]] uint4 xt_a[XT_ITEMS], xt_b[XT_ITEMS];
+    [[maybe_unused]] float xt_w0[XT_ITEMS], xt_w1[XT_ITEMS];
+    if constexpr (EPI == EPI_SIGN_XT) {
+      constexpr int CH = WN / 8;
+      const bf16_bits* Xb = Ab + g.a_seg[0];
+      const float* wrow = g.xt_w + (int64_t)bz * g.xt_ldw;
+#pragma unroll
+      for (int q = 0; q < XT_ITEMS; ++q) {
+        const int item = q * 64 + lane, c = item % CH, p = item / CH;
+        const int m = mw + 2 * p, k = nw + 8 * c;
+        xt_a[q] = make_uint4(0u, 0u, 0u, 0u); xt_b[q] = xt_a[q];
+        xt_w0[q] = 0.0f; xt_w1[q] = 0.0f;
+        if (k < g.N) {
+          if (m < g.M) { xt_a[q] = *reinterpret_cast<const uint4*>(Xb + (int64_t)m * g.lda + k); xt_w0[q] = wrow[m]; }
+          if (m + 1 < g.M) { xt_b[q] = *reinterpret_cast<const uint4*>(Xb + (int64_t)(m + 1) * g.lda + k); xt_w1[q] = wrow[m + 1]; }
+        }
+      }
+    }
     __syncthreads();                                  // every wavefront has finished reading operand tiles
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -327,6 +347,57 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
       const int n = nw + r, m = mw + c * 8;
       const uint4 v = *reinterpret_cast<const uint4*>(stg + r * SROW + ((c ^ (r & (CPR - 1))) << 4));
       if (n < g.N && m < g.st_rows_valid) *reinterpret_cast<uint4*>(St + (int64_t)n * g.ldc + m) = v;
+    }
+    if constexpr (EPI == EPI_SIGN_XT) {
+      // The scaled, transposed fp16 copy of A's block under this wavefront's output block: tokens [mw, mw + WM) x
+      // channels [nw, nw + WN).  A lane takes items (token pair p, 16-byte chunk c of 8 channels), chunk fastest so
+      // that 8 lanes read 128 contiguous bytes of a row; the pair's two values of a channel go to the staging slice as
+      // one 4-byte write (row = channel, position = token pair); 16-byte chunks of 8 tokens come back and are stored
+      // like the signs.  The slice is this wavefront's own and LDS operations of one wavefront complete in order, so
+      // no barrier separates this from the sign staging above.
+      constexpr int PAIRS = WM / 2, CH = WN / 8;
+      static_assert((PAIRS * CH) % 64 == 0, "whole wavefronts of items");
+      const float* wrow = g.xt_w + (int64_t)bz * g.xt_ldw;
+      bf16_bits* Xt = g.Xt + (int64_t)bz * g.batchC;
+      auto phys = [](int r, int cc) { return cc ^ ((r ^ (r >> 3)) & (CPR - 1)); };
+#pragma unroll
+      for (int q = 0; q < PAIRS * CH / 64; ++q) {
+        const int item = q * 64 + lane, c = item % CH, p = item / CH;
+        const uint4 xa = xt_a[q], xb = xt_b[q];
+        const float w0 = xt_w0[q], w1 = xt_w1[q];
+        const uint32_t ua[4] = {xa.x, xa.y, xa.z, xa.w}, ub[4] = {xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t ba = (e & 1) ? (ua[e >> 1] & 0xffff0000u) : (ua[e >> 1] << 16);
+          const uint32_t bb = (e & 1) ? (ub[e >> 1] & 0xffff0000u) : (ub[e >> 1] << 16);
+          // a skipped row has w = 0 and possibly Inf / NaN values: select, do not multiply
+          const float fa = w0 != 0.0f ? __uint_as_float(ba) * w0 : 0.0f;
+          const float fb = w1 != 0.0f ? __uint_as_float(bb) * w1 : 0.0f;
+          const int r = c * 8 + e;
+          *reinterpret_cast<uint32_t*>(stg + r * SROW + (phys(r, p >> 2) << 4) + (p & 3) * 4) = f32x2_to_f16x2(fa, fb);
+        }
+      }
+#pragma unroll
+      for (int it2 = 0; it2 < WN * CPR / 64; ++it2) {
+        const int idx = it2 * 64 + lane, r = idx / CPR, cc = idx % CPR;
+        const int n = nw + r, m = mw + cc * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(stg + r * SROW + (phys(r, cc) << 4));
+        if (n < g.N && m < g.st_rows_valid) *reinterpret_cast<uint4*>(Xt + (int64_t)n * g.ldc + m) = v;
+      }
+      if (tn == 0 && wn == 0) {   // one wavefront per 64 tokens of the tile row counts them
+#pragma unroll
+        for (int t0 = 0; t0 < WM; t0 += 64) {
+          const int m = mw + t0 + lane;
+          const bool in_block = t0 + lane < WM && m < g.M;
+          const float wv = in_block ? wrow[m] : 0.0f;
+          const unsigned long long in = __ballot(in_block && wv != 0.0f), out = __ballot(in_block && wv == 0.0f);
+          if (lane == 0) {
+            unsigned long long* slot = g.cnt + ((int64_t)bz * g.cnt_slots + (tm % g.cnt_slots)) * 2;
+            if (in) atomicAdd(slot, (unsigned long long)__popcll(in));
+            if (out) atomicAdd(slot + 1, (unsigned long long)__popcll(out));
+          }
+        }
+      }
     }
   } else if constexpr (EPI == EPI_ACT) {
 #pragma unroll
@@ -688,6 +759,9 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
   if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_SIGN: return launch_epi<EPI_SIGN>(a, batch, stream);
+    case EPI_SIGN_XT:
+      if (!a.xt_w || !a.Xt || !a.cnt || a.cnt_slots < 1 || a.N != a.K || a.nseg != 1) return hipErrorInvalidValue;
+      return launch_epi<EPI_SIGN_XT>(a, batch, stream);
     case EPI_SIGN_ACT: return a.Yact ? launch_epi<EPI_SIGN_ACT>(a, batch, stream) : hipErrorInvalidValue;
     case EPI_ACT: return launch_epi<EPI_ACT>(a, batch, stream);
     case EPI_F32: return a.ab_f16 ? launch_epi<EPI_F32, true>(a, batch, stream) : launch_epi<EPI_F32>(a, batch, stream);

@@ -125,6 +125,23 @@ def test_full_batch_elementwise(B, name):
         A = M.astype(np.float32).astype(np.float64) + w.prox_lambda * tau * R0[0].astype(np.float64)
         say(f"  {name}: update iters={ust[0]['iters']} ms={ust[0]['ms']:.3f} device orth={ust[0]['orth_err']:.2e}")
         polar_properties(R[0], A, f"{name} polar")
+        # the same M at prox_lambda = 0, i.e. the limit lambda -> 0+ (the paper's R <- U V^T on the range of M, the
+        # completion nearest R_prev on its null space): M has rank <= T < d here, so the optimum of <R, M> is the nuclear
+        # norm of M itself, reached by every completion
+        cal0 = B.Calibrator(d, 1, w.dtype, R0, max_tokens=64, prox_lambda=0.0)
+        try:
+            cal0.set_state(M=M.astype(np.float32))
+            _, u0 = cal0.update_rotation()
+            Rz, _, _ = cal0.get_state(want_M=False)
+            R64 = Rz[0].astype(np.float64)
+            M32 = M.astype(np.float32).astype(np.float64)
+            nuc = np.linalg.svd(M32, compute_uv=False).sum()
+            got = float((R64 * M32).sum())
+            orth = np.linalg.norm(R64.T @ R64 - np.eye(d))
+            say(f"  {name} lambda -> 0+: iters={u0[0]['iters']} ms={u0[0]['ms']:.3f} orth={orth:.2e} <R,M>={got:.6e} nuclear={nuc:.6e}")
+            assert orth <= 1e-4 and abs(got - nuc) <= 1e-3 * nuc
+        finally:
+            cal0.close()
         # the next batch from the LEARNED rotation: the GPU's updated R becomes the oracle's state
         oc.reset_stats()
         oc.R[:] = R

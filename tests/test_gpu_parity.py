@@ -709,6 +709,9 @@ def test_error_paths(B):
         with pytest.raises(B.ConqurError) as e:
             cal.step_batch(X)                                                       # T > max_tokens
         assert e.value.status == B.EINVAL
+        with pytest.raises(B.ConqurError) as e:
+            cal.step_batch(X[:0])                                                   # an empty batch
+        assert e.value.status == B.EINVAL
         with pytest.raises(ValueError):
             cal.step_batch(X[:8, :32])                                              # fewer than d columns
         with pytest.raises(B.ConqurError) as e:                                     # row pitch < d, at the C ABI
