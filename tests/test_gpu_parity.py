@@ -605,6 +605,35 @@ def test_batched_update_of_many_layers_fills_the_device(B):
         big.close()
 
 
+@pytest.mark.parametrize("d,heads,dtype", [(320, 1, "bf16"), (256, 2, "bf16"), (128, 1, "f32")])
+def test_rows_with_a_pitch_wider_than_d(B, d, heads, dtype):
+    """X as a view into a wider buffer (row pitch d + 24 elements, base 16 columns in): every kernel that reads X --
+    norms, rotate GEMM and its transposing epilogue, the per-head step, the split planes -- must honour the pitch."""
+    import torch
+    T = 210
+    w = I.small_workload(d, T, n_batches=1, heads=heads, dtype=dtype, seed=808 + d, massive_frac=0.01)
+    X = I.batch(w, 0)
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(d, heads, dtype, R0)
+    oc.step_batch(X)
+    cal = B.Calibrator(d, heads, dtype, R0, max_tokens=T)
+    try:
+        wide = torch.full((T, d + 24), 7.0, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda:0")
+        wide[:, 16:16 + d] = B.to_device(X, dtype)
+        view = wide[:, 16:16 + d]
+        cal.step_batch(view)
+        _, Mg, n_rows = cal.get_state(want_R=False)
+        for h in range(heads):
+            relM = np.linalg.norm(Mg[h] - oc.M[h]) / np.linalg.norm(oc.M[h])
+            assert relM <= TOL_M, (h, relM)
+        assert np.array_equal(n_rows, oc.n)
+        so, eo, _, _ = oc.quant_error(X, 4)
+        sg, eg = cal.quant_error(view, 4)
+        assert abs(sg - so) <= TOL_REL * so and abs(eg - eo) <= TOL_REL * eo
+    finally:
+        cal.close()
+
+
 def test_pooled_batches_before_one_update(B):
     """Alg. 1 pools several sites into one update: three step_batch calls (shrinking T), one update."""
     w = I.small_workload(256, 384, n_batches=3, seed=77, prox_lambda=0.0)
