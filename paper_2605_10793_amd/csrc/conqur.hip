@@ -98,6 +98,7 @@ struct conqur_ctx {
   hipEvent_t ev[ST_COUNT][2]{};
   bool ev_valid[ST_COUNT]{};
   hipEvent_t ev_resid = nullptr;   // behind the copy of a closing residual: the host waits for this, not for the stream
+  hipEvent_t ev_sq = nullptr;      // behind the copy of ||D^2||_F^2 of the closing step's D^2 product
   double* host_res = nullptr;      // pinned: [kResidSlots][heads] residual history, then the update's result block
   float* host_rows = nullptr;      // pinned: per-row errors and energies of one score call (up to kHostSumRows rows)
   std::vector<void*> allocs;
@@ -191,6 +192,7 @@ void conqur_destroy(conqur_ctx* ctx) {
     for (int k = 0; k < 2; ++k)
       if (ctx->ev[s][k]) (void)hipEventDestroy(ctx->ev[s][k]);
   if (ctx->ev_resid) (void)hipEventDestroy(ctx->ev_resid);
+  if (ctx->ev_sq) (void)hipEventDestroy(ctx->ev_sq);
   if (ctx->host_res) (void)hipHostFree(ctx->host_res);
   if (ctx->host_rows) (void)hipHostFree(ctx->host_rows);
   delete ctx;
@@ -281,6 +283,7 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
     for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreate(&ctx->ev[s][k]);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_resid, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_sq, hipEventDisableTiming);
   if (e == hipSuccess)
     e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_res), ((size_t)kResidSlots * ctx->heads + 3 * ctx->heads + 1) * sizeof(double),
                       hipHostMallocDefault);
@@ -672,6 +675,9 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     return e;
   };
   // W2 = D + 1.5 D^2 from the planes of D = (I - G)/2 in PW (D is symmetric, so D D^T = D^2)
+  // keep_square: D^2 itself is kept as a plane and ||D^2||_F^2 goes to residual slot `slot` (copied to the host behind
+  // ev_sq): both serve the orthogonality bounds of the step that applies this correction.
+  int sq_slot = -1;
   auto square_correction = [&](bool keep_square) -> hipError_t {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
@@ -681,9 +687,17 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.ldc = dh; g.batchC = blk; g.Pn = ctx->PW2; g.np_out = 2; g.plane_out = plane;
     g.Padd = ctx->PW; g.np_add = 2; g.coef_i = 0.0f; g.coef_g = 1.5f;
     g.symmetric = 1;
+    sq_slot = -1;
     if (!keep_square) return launch_gemm_nt(g, EPI_GRAMW, h, s);
     g.Pacc = ctx->PW2 + 2 * plane;   // D^2 itself, third plane of the buffer
-    return launch_gemm_nt(g, EPI_SQUARE, h, s);
+    g.resid_part = ctx->resid_part;
+    hipError_t e = launch_gemm_nt(g, EPI_SQUARE, h, s);
+    if (e == hipSuccess) e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(ctx->host_res + (size_t)slot * h, ctx->resid + (size_t)slot * h, h * sizeof(double), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipEventRecord(ctx->ev_sq, s);
+    if (e == hipSuccess) sq_slot = slot++;
+    return e;
   };
   // ||D^3||_F^2 (into residual slot `slot`) from the planes of D and D^2: the quintic step leaves the residual
   // I - X'^T X' = 5 D^3 + 3.75 D^4 + 4.5 D^5 (both sides polynomials in D), so this norm predicts it.
@@ -849,6 +863,26 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       // (kCubeFactor = 5.5 also covers the bf16 rounding of the D^3 product),
       // plus the rounding of the correction product and of the fp32 iterate (kOrthFloor per unit of dh,
       // calibrated against the measured residual).
+      // First from what the D^2 product left behind, without another GEMM: D is symmetric, so ||D||_2^2 = ||D^2||_2
+      // <= ||D^2||_F and ||D^3||_F <= ||D||_2 ||D^2||_F <= ||D^2||_F^(3/2).  Looser than the norm itself by about
+      // dh^(1/4), which the tolerance still accommodates up to dh of a few thousand.
+      if (sq_slot >= 0 && !ctx->cfg.polar_verify) {
+        HIP_TRY(hipEventSynchronize(ctx->ev_sq));
+        double worst = 0.0;
+        for (int q = 0; q < h; ++q) worst = std::max(worst, std::sqrt(hist[(size_t)sq_slot * h + q]));
+        const double pred1 = kCubeFactor * std::pow(worst, 1.5) + kOrthFloorPerDim * dh;
+        if (trace) std::fprintf(stderr, "[conqur] polar closing: ||D^2||_F=%.4e bound on resid_F=%.4e\n", worst, pred1);
+        if (std::isfinite(pred1) && pred1 <= tol) {
+          for (int q = 0; q < h; ++q) {
+            const double b = kCubeFactor * std::pow(std::sqrt(hist[(size_t)sq_slot * h + q]), 1.5) + kOrthFloorPerDim * dh;
+            hist[(size_t)sq_slot * h + q] = b * b;
+          }
+          last_slot = sq_slot;
+          converged = true;
+          predicted = true;
+          break;
+        }
+      }
       HIP_TRY(cube_norm());
       const int cslot = slot++;
       st = post_resid(cslot);

@@ -19,7 +19,7 @@ enum GemmEpilogue : int {
   EPI_XOUT = 4,  // acc = X' (+ Xadd): written as fp32 (C32) and/or np_out bf16 split planes in natural (Pn)
                  // and transposed (Pt) layout -- the operands of the next Gram / apply GEMMs
   EPI_SQUARE = 5, // acc = D^2 (D symmetric, given as two planes Padd): writes acc as one bf16 plane (Pacc) and
-                  // coef_g * acc + D as two split planes (Pn)
+                  // coef_g * acc + D as two split planes (Pn); per-wavefront partial sums of acc^2 (resid_part) if asked
   EPI_FRO2 = 6,   // per-wavefront partial sums of acc^2 only (resid_part): a Frobenius norm, nothing stored
   EPI_XLAST = 7,  // acc = X' rounded to np_out (1 or 2) bf16 split planes: exactly that value goes to C32 (fp32), to
                   // np_out natural planes (Pn) and to np_out transposed planes (Pt) -- the hand-over from the

@@ -491,12 +491,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   } else if constexpr (EPI == EPI_SQUARE) {
     const int64_t boff = (int64_t)bz * g.batchC;
     [[maybe_unused]] const bool mirror = SYM && tm != tn;
+    double rsum = 0.0;   // sum of the squares of this wavefront's accumulators: ||D^2||_F^2 over the whole launch
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int n = nw + j * 32 + col;
         if (n >= g.N) continue;
+        float part = 0.0f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int mb = mw + i * 32 + 8 * q + 4 * half;
@@ -506,6 +508,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           for (int r = 0; r < 4; ++r) {
             const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
             a[r] = acc[i][j][4 * q + r];
+            part += a[r] * a[r];
             w[r] = g.coef_g * a[r] + bf16_to_f32(g.Padd[off]) + bf16_to_f32(g.Padd[g.plane_out + off]);
           }
           uint2 ta, t0, t1;
@@ -532,7 +535,17 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
             }
           }
         }
+        rsum += (double)part;
       }
+    if (g.resid_part) {
+      rsum = wave_sum_d(rsum);
+      if (lane == 0) {
+        g.resid_part[((int64_t)bz * ntiles + tn * tiles_m + tm) * NW + wave] = rsum;
+        if constexpr (SYM) {   // a tile above the diagonal stands for its mirror image as well
+          if (mirror) g.resid_part[((int64_t)bz * ntiles + tm * tiles_m + tn) * NW + wave] = rsum;
+        }
+      }
+    }
   } else if constexpr (EPI == EPI_FRO2) {
     double rsum = 0.0;
 #pragma unroll
