@@ -16,6 +16,8 @@
 // measured SQ_LDS_BANK_CONFLICT = 0.
 #include "gemm_nt.h"
 
+#include <type_traits>
+
 namespace conqur {
 
 namespace {
@@ -279,6 +281,59 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   //   m = m0 + wm*WM + im*32 + 8*j + 4*half + i,   column n = n0 + wn*WN + in*32 + col.
   const int mw = m0 + wm * WM, nw = n0 + wn * WN;
 
+  // Addressing of the epilogues that write matrices [row][ldc]: buffer instructions with 32-bit byte offsets, so that
+  // a store is one instruction (no 64-bit address arithmetic per element) and bounds need no branches.  An offset at
+  // or beyond the range of its array (rows past the last one; kOobOffset for lanes whose column, or whose rows in the
+  // transposed layout, do not exist) makes a store a no-op and a load return zero.  With the per-element pointer
+  // arithmetic and branches these epilogues ran 4000-5000 instructions per wavefront for 128 values per lane, and
+  // instruction issue, not memory, was what they waited for.
+  //   natural layout     [m][n]: byte offset nat{2,4}[j] + row_off(rows below the lane's first) * element size
+  //   transposed layout  [n][m]: byte offset tr_off(j, rows below the lane's first), 4 consecutive m = 8 bytes
+  [[maybe_unused]] const uint32_t ldc_u = (uint32_t)g.ldc;
+  [[maybe_unused]] const uint32_t nat_rows = (uint32_t)g.M * ldc_u, tr_rows = (uint32_t)g.N * ldc_u;   // elements
+  [[maybe_unused]] const int mlim = g.M - (mw + 4 * half);   // rows ml .. ml + 3 of this lane exist iff ml < mlim
+  [[maybe_unused]] bool n_ok[TN];
+  [[maybe_unused]] uint32_t nat2[TN], nat4[TN], tr2[TN];
+  {
+    const uint32_t lane_nat = (uint32_t)(mw + 4 * half) * ldc_u + (uint32_t)(nw + col);
+    const uint32_t lane_tr = (uint32_t)(nw + col) * ldc_u + (uint32_t)(mw + 4 * half);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      n_ok[j] = nw + 32 * j + col < g.N;
+      nat2[j] = n_ok[j] ? (lane_nat + 32u * j) * 2u : kOobOffset;
+      nat4[j] = n_ok[j] ? (lane_nat + 32u * j) * 4u : kOobOffset;
+      tr2[j] = (lane_tr + 32u * j * ldc_u) * 2u;   // columns n >= N are rows past the end of the transposed array
+    }
+  }
+  [[maybe_unused]] auto row_off = [&](int ml) { return (uint32_t)ml * ldc_u; };
+  [[maybe_unused]] auto tr_off = [&](int j, int ml) { return ml < mlim ? tr2[j] + 2u * (uint32_t)ml : kOobOffset; };
+  [[maybe_unused]] auto out_rsrc = [](void* p, uint32_t bytes) { return __builtin_amdgcn_make_buffer_rsrc(p, 0, (int)bytes, 0x00020000); };
+  [[maybe_unused]] auto in_rsrc = [](const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+  };
+  [[maybe_unused]] auto ld32 = [](__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+  };
+  [[maybe_unused]] auto ld16 = [](__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return (bf16_bits)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+  };
+  [[maybe_unused]] auto st32 = [](__amdgpu_buffer_rsrc_t r, uint32_t off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, off, 0, 0);
+  };
+  [[maybe_unused]] auto st64 = [](__amdgpu_buffer_rsrc_t r, uint32_t off, const uint2& t) {
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 v = {t.x, t.y};
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, 0);
+  };
+  // the 4 packed 16-bit values of t to rows 0 .. 3 below byte offset off of a natural-layout plane
+  [[maybe_unused]] auto st_rows4 = [&](__amdgpu_buffer_rsrc_t r, uint32_t off, const uint2& t) {
+    const uint32_t rb = 2u * ldc_u;
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)t.x, r, off, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(t.x >> 16), r, off + rb, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)t.y, r, off + 2u * rb, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(t.y >> 16), r, off + 3u * rb, 0, 0);
+  };
+
   if constexpr (EPI == EPI_SIGN_ACT) {   // the rotated rows themselves, as EPI_ACT writes them
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -416,69 +471,81 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
         }
       }
   } else if constexpr (EPI == EPI_F32) {
-    float* C = reinterpret_cast<float*>(g.C) + (int64_t)bz * g.batchC;
+    const auto rC = out_rsrc(reinterpret_cast<float*>(g.C) + (int64_t)bz * g.batchC, nat_rows * 4u);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
+        float v[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m >= g.M) continue;
-          float* p = C + (int64_t)m * g.ldc + n;
-          const float v = g.out_scale * acc[i][j][e];
-          *p = g.accumulate ? (*p + v) : v;
+        for (int e = 0; e < 16; ++e) v[e] = g.out_scale * acc[i][j][e];
+        if (g.accumulate) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) v[e] += ld32(rC, nat4[j] + row_off(32 * i + 8 * (e >> 2) + (e & 3)) * 4u);
         }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st32(rC, nat4[j] + row_off(32 * i + 8 * (e >> 2) + (e & 3)) * 4u, v[e]);
       }
   } else if constexpr (EPI == EPI_GRAMW) {
     const int64_t boff = (int64_t)bz * g.batchC;
     [[maybe_unused]] const bool mirror = SYM && tm != tn;   // this tile is also the transpose of tile (tn, tm)
     double rsum = 0.0;
+    // Only a workgroup whose tile meets the diagonal has entries of the identity to add and subtract: the others run
+    // the version of the code without them (a wave-uniform choice).
+    auto tiles = [&](auto on_diagonal) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
-        float part = 0.0f;
+        for (int j = 0; j < TN; ++j) {
+          float part = 0.0f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int mb = mw + i * 32 + 8 * q + 4 * half;   // rows mb .. mb + 3 (M is a multiple of 4)
-          if (mb >= g.M) continue;
-          float w[4];
+          for (int q = 0; q < 4; ++q) {
+            const int ml = 32 * i + 8 * q;            // rows ml .. ml + 3 of this lane's block (M is a multiple of 4)
+            float w[4], part_q = 0.0f;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float a = acc[i][j][4 * q + r];
-            const float eye = (mb + r == n) ? 1.0f : 0.0f;
-            const float d = a - eye;
-            part += d * d;
-            w[r] = g.coef_i * eye + g.coef_g * a;
-            const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
-            for (int p = 0; p < g.np_add; ++p) w[r] += bf16_to_f32(g.Padd[p * g.plane_out + off]);
-          }
-          for (int p = 0; p < (F16 ? 1 : g.np_out); ++p) {
-            uint2 t;
-            if constexpr (F16) {   // fp16 operands: the factor is one fp16 plane
-              t.x = f32x2_to_f16x2(w[0], w[1]);
-              t.y = f32x2_to_f16x2(w[2], w[3]);
-            } else {
-              t.x = f32x2_to_bf16x2(w[0], w[1]);
-              t.y = f32x2_to_bf16x2(w[2], w[3]);
-              w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
-              w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
+            for (int r = 0; r < 4; ++r) {
+              const float a = acc[i][j][4 * q + r];
+              if constexpr (decltype(on_diagonal)::value) {
+                const float eye = (mw + 4 * half + ml + r == nw + 32 * j + col) ? 1.0f : 0.0f;
+                const float d = a - eye;
+                part_q += d * d;
+                w[r] = g.coef_i * eye + g.coef_g * a;
+              } else {
+                part_q += a * a;
+                w[r] = g.coef_g * a;
+              }
             }
-            bf16_bits* pn = g.Pn + p * g.plane_out + boff + (int64_t)mb * g.ldc + n;
-            pn[0] = (bf16_bits)t.x; pn[g.ldc] = (bf16_bits)(t.x >> 16);
-            pn[2 * g.ldc] = (bf16_bits)t.y; pn[3 * g.ldc] = (bf16_bits)(t.y >> 16);
-            if constexpr (SYM) {
-              if (mirror) *reinterpret_cast<uint2*>(g.Pn + p * g.plane_out + boff + (int64_t)n * g.ldc + mb) = t;
+            part += (n_ok[j] && ml < mlim) ? part_q : 0.0f;
+            if constexpr (!F16) {   // (fp16 operands: no planes to add)
+              for (int p = 0; p < g.np_add; ++p) {
+                const auto rA = in_rsrc(g.Padd + p * g.plane_out + boff, nat_rows * 2u);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) w[r] += bf16_to_f32(ld16(rA, nat2[j] + row_off(ml + r) * 2u));
+              }
+            }
+            for (int p = 0; p < (F16 ? 1 : g.np_out); ++p) {
+              uint2 t;
+              if constexpr (F16) {   // fp16 operands: the factor is one fp16 plane
+                t.x = f32x2_to_f16x2(w[0], w[1]);
+                t.y = f32x2_to_f16x2(w[2], w[3]);
+              } else {
+                t.x = f32x2_to_bf16x2(w[0], w[1]);
+                t.y = f32x2_to_bf16x2(w[2], w[3]);
+                w[0] -= __uint_as_float(t.x << 16); w[1] -= __uint_as_float(t.x & 0xffff0000u);
+                w[2] -= __uint_as_float(t.y << 16); w[3] -= __uint_as_float(t.y & 0xffff0000u);
+              }
+              const auto rP = out_rsrc(g.Pn + p * g.plane_out + boff, nat_rows * 2u);
+              st_rows4(rP, nat2[j] + row_off(ml) * 2u, t);
+              if constexpr (SYM) {
+                if (mirror) st64(rP, tr_off(j, ml), t);
+              }
             }
           }
+          rsum += (double)part;
         }
-        rsum += (double)part;
-      }
+    };
+    if (m0 < n0 + BN && n0 < m0 + BM) tiles(std::true_type{});
+    else tiles(std::false_type{});
     if (g.resid_part) {
       rsum = wave_sum_d(rsum);
       if (lane == 0) {
@@ -491,25 +558,26 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   } else if constexpr (EPI == EPI_SQUARE) {
     const int64_t boff = (int64_t)bz * g.batchC;
     [[maybe_unused]] const bool mirror = SYM && tm != tn;
+    const auto rA0 = in_rsrc(g.Padd + boff, nat_rows * 2u), rA1 = in_rsrc(g.Padd + g.plane_out + boff, nat_rows * 2u);
+    const auto rSq = out_rsrc(g.Pacc + boff, nat_rows * 2u);
+    const auto rW0 = out_rsrc(g.Pn + boff, nat_rows * 2u), rW1 = out_rsrc(g.Pn + g.plane_out + boff, nat_rows * 2u);
     double rsum = 0.0;   // sum of the squares of this wavefront's accumulators: ||D^2||_F^2 over the whole launch
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
         float part = 0.0f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int mb = mw + i * 32 + 8 * q + 4 * half;
-          if (mb >= g.M) continue;
+          const int ml = 32 * i + 8 * q;
+          const bool in = n_ok[j] && ml < mlim;
           float a[4], w[4];
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
+            const uint32_t off = nat2[j] + row_off(ml + r) * 2u;
             a[r] = acc[i][j][4 * q + r];
-            part += a[r] * a[r];
-            w[r] = g.coef_g * a[r] + bf16_to_f32(g.Padd[off]) + bf16_to_f32(g.Padd[g.plane_out + off]);
+            part += in ? a[r] * a[r] : 0.0f;
+            w[r] = g.coef_g * a[r] + bf16_to_f32(ld16(rA0, off)) + bf16_to_f32(ld16(rA1, off));
           }
           uint2 ta, t0, t1;
           ta.x = f32x2_to_bf16x2(a[0], a[1]);
@@ -518,20 +586,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
           t0.y = f32x2_to_bf16x2(w[2], w[3]);
           t1.x = f32x2_to_bf16x2(w[0] - __uint_as_float(t0.x << 16), w[1] - __uint_as_float(t0.x & 0xffff0000u));
           t1.y = f32x2_to_bf16x2(w[2] - __uint_as_float(t0.y << 16), w[3] - __uint_as_float(t0.y & 0xffff0000u));
-          const int64_t off = boff + (int64_t)mb * g.ldc + n;
-          auto rows4 = [&](bf16_bits* base, const uint2& t) {
-            base[0] = (bf16_bits)t.x; base[g.ldc] = (bf16_bits)(t.x >> 16);
-            base[2 * g.ldc] = (bf16_bits)t.y; base[3 * g.ldc] = (bf16_bits)(t.y >> 16);
-          };
-          rows4(g.Pacc + off, ta);
-          rows4(g.Pn + off, t0);
-          rows4(g.Pn + g.plane_out + off, t1);
+          const uint32_t off = nat2[j] + row_off(ml) * 2u;
+          st_rows4(rSq, off, ta);
+          st_rows4(rW0, off, t0);
+          st_rows4(rW1, off, t1);
           if constexpr (SYM) {
             if (mirror) {
-              const int64_t offt = boff + (int64_t)n * g.ldc + mb;
-              *reinterpret_cast<uint2*>(g.Pacc + offt) = ta;
-              *reinterpret_cast<uint2*>(g.Pn + offt) = t0;
-              *reinterpret_cast<uint2*>(g.Pn + g.plane_out + offt) = t1;
+              const uint32_t offt = tr_off(j, ml);
+              st64(rSq, offt, ta);
+              st64(rW0, offt, t0);
+              st64(rW1, offt, t1);
             }
           }
         }
@@ -552,13 +616,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
         float part = 0.0f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m < g.M) part += acc[i][j][e] * acc[i][j][e];
+          const bool in = n_ok[j] && 32 * i + 8 * (e >> 2) + (e & 3) < mlim;
+          part += in ? acc[i][j][e] * acc[i][j][e] : 0.0f;
         }
         rsum += (double)part;
       }
@@ -572,84 +634,80 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
   } else if constexpr (EPI == EPI_XLAST) {
     const int64_t boff = (int64_t)bz * g.batchC;
     const bool two = g.np_out == 2;
+    const auto rC = out_rsrc(g.C32 + boff, nat_rows * 4u);
+    const auto rN0 = out_rsrc(g.Pn + boff, nat_rows * 2u), rN1 = out_rsrc(g.Pn + g.plane_out + boff, two ? nat_rows * 2u : 0u);
+    const auto rT0 = out_rsrc(g.Pt + boff, tr_rows * 2u), rT1 = out_rsrc(g.Pt + g.plane_out + boff, two ? tr_rows * 2u : 0u);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int mb = mw + i * 32 + 8 * q + 4 * half;   // 4 consecutive rows mb .. mb+3 (M is a multiple of 4)
-          if (mb >= g.M) continue;
+          const int ml = 32 * i + 8 * q;
           const float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
           uint2 hi;
           hi.x = f32x2_to_bf16x2(v0, v1);
           hi.y = f32x2_to_bf16x2(v2, v3);
           float h0 = __uint_as_float(hi.x << 16), h1 = __uint_as_float(hi.x & 0xffff0000u);
           float h2 = __uint_as_float(hi.y << 16), h3 = __uint_as_float(hi.y & 0xffff0000u);
-          const int64_t off = boff + (int64_t)mb * g.ldc + n;
-          bf16_bits* pn = g.Pn + off;
-          bf16_bits* pt = g.Pt + boff + (int64_t)n * g.ldc + mb;
-          pn[0] = (bf16_bits)hi.x; pn[g.ldc] = (bf16_bits)(hi.x >> 16);
-          pn[2 * g.ldc] = (bf16_bits)hi.y; pn[3 * g.ldc] = (bf16_bits)(hi.y >> 16);
-          *reinterpret_cast<uint2*>(pt) = hi;
+          const uint32_t off = nat2[j] + row_off(ml) * 2u, offt = tr_off(j, ml);
+          st_rows4(rN0, off, hi);
+          st64(rT0, offt, hi);
           if (two) {
             uint2 lo;
             lo.x = f32x2_to_bf16x2(v0 - h0, v1 - h1);
             lo.y = f32x2_to_bf16x2(v2 - h2, v3 - h3);
-            pn += g.plane_out;
-            pn[0] = (bf16_bits)lo.x; pn[g.ldc] = (bf16_bits)(lo.x >> 16);
-            pn[2 * g.ldc] = (bf16_bits)lo.y; pn[3 * g.ldc] = (bf16_bits)(lo.y >> 16);
-            *reinterpret_cast<uint2*>(pt + g.plane_out) = lo;
+            st_rows4(rN1, off, lo);
+            st64(rT1, offt, lo);
             // hi + lo has at most 17 significant bits: the fp32 sums are exact
             h0 += __uint_as_float(lo.x << 16); h1 += __uint_as_float(lo.x & 0xffff0000u);
             h2 += __uint_as_float(lo.y << 16); h3 += __uint_as_float(lo.y & 0xffff0000u);
           }
-          g.C32[off] = h0;
-          g.C32[off + g.ldc] = h1;
-          g.C32[off + 2 * g.ldc] = h2;
-          g.C32[off + 3 * g.ldc] = h3;
+          st32(rC, nat4[j] + row_off(ml) * 4u, h0);
+          st32(rC, nat4[j] + row_off(ml + 1) * 4u, h1);
+          st32(rC, nat4[j] + row_off(ml + 2) * 4u, h2);
+          st32(rC, nat4[j] + row_off(ml + 3) * 4u, h3);
         }
       }
   } else {  // EPI_XOUT
     const int64_t boff = (int64_t)bz * g.batchC;
+    // an absent array gets an empty range: its loads return zero and its stores are dropped
+    const auto rX = in_rsrc(g.Xadd ? g.Xadd + boff : nullptr, g.Xadd ? nat_rows * 4u : 0u);
+    const auto rC = out_rsrc(g.C32 ? g.C32 + boff : nullptr, g.C32 ? nat_rows * 4u : 0u);
+    const int np_max = F16 ? 1 : (g.np_out > g.np_out_n ? g.np_out : g.np_out_n);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
+        float v[16];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int mb = mw + i * 32 + 8 * q + 4 * half;   // 4 consecutive rows mb .. mb+3 (M is a multiple of 4)
-          if (mb >= g.M) continue;
-          float v[4];
+        for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+        if (g.Xadd) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            v[r] = acc[i][j][4 * q + r];
-            const int64_t off = boff + (int64_t)(mb + r) * g.ldc + n;
-            if (g.Xadd) v[r] += g.Xadd[off];
-            if (g.C32) g.C32[off] = v[r];
-          }
-          const int np_max = F16 ? 1 : (g.np_out > g.np_out_n ? g.np_out : g.np_out_n);
-          for (int p = 0; p < np_max; ++p) {
-            uint2 t;   // the 4 values as bf16, packed; the remainder goes on to the next plane
+          for (int e = 0; e < 16; ++e) v[e] += ld32(rX, nat4[j] + row_off(32 * i + 8 * (e >> 2) + (e & 3)) * 4u);
+        }
+        if (g.C32) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) st32(rC, nat4[j] + row_off(32 * i + 8 * (e >> 2) + (e & 3)) * 4u, v[e]);
+        }
+        for (int p = 0; p < np_max; ++p) {
+          const auto rN = out_rsrc(g.Pn + p * g.plane_out + boff, p < g.np_out_n ? nat_rows * 2u : 0u);
+          const auto rT = out_rsrc(g.Pt + p * g.plane_out + boff, p < g.np_out ? tr_rows * 2u : 0u);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int ml = 32 * i + 8 * q;
+            uint2 t;   // the 4 values of rows ml .. ml + 3, packed; the remainder goes on to the next plane
             if constexpr (F16) {   // fp16 operands: the iterate is one fp16 plane of each layout
-              t.x = f32x2_to_f16x2(v[0], v[1]);
-              t.y = f32x2_to_f16x2(v[2], v[3]);
+              t.x = f32x2_to_f16x2(v[4 * q], v[4 * q + 1]);
+              t.y = f32x2_to_f16x2(v[4 * q + 2], v[4 * q + 3]);
             } else {
-              t.x = f32x2_to_bf16x2(v[0], v[1]);
-              t.y = f32x2_to_bf16x2(v[2], v[3]);
-              v[0] -= __uint_as_float(t.x << 16); v[1] -= __uint_as_float(t.x & 0xffff0000u);
-              v[2] -= __uint_as_float(t.y << 16); v[3] -= __uint_as_float(t.y & 0xffff0000u);
+              t.x = f32x2_to_bf16x2(v[4 * q], v[4 * q + 1]);
+              t.y = f32x2_to_bf16x2(v[4 * q + 2], v[4 * q + 3]);
+              v[4 * q] -= __uint_as_float(t.x << 16); v[4 * q + 1] -= __uint_as_float(t.x & 0xffff0000u);
+              v[4 * q + 2] -= __uint_as_float(t.y << 16); v[4 * q + 3] -= __uint_as_float(t.y & 0xffff0000u);
             }
-            if (p < g.np_out_n) {
-              bf16_bits* q = g.Pn + p * g.plane_out + boff + (int64_t)mb * g.ldc + n;
-              q[0] = (bf16_bits)t.x; q[g.ldc] = (bf16_bits)(t.x >> 16);
-              q[2 * g.ldc] = (bf16_bits)t.y; q[3 * g.ldc] = (bf16_bits)(t.y >> 16);
-            }
-            if (p < g.np_out) *reinterpret_cast<uint2*>(g.Pt + p * g.plane_out + boff + (int64_t)n * g.ldc + mb) = t;
+            st_rows4(rN, nat2[j] + row_off(ml) * 2u, t);
+            st64(rT, tr_off(j, ml), t);
           }
         }
       }
@@ -768,6 +826,10 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
     return hipErrorInvalidValue;
   if (a.symmetric && ((epi != EPI_GRAMW && epi != EPI_SQUARE && epi != EPI_FRO2) || (epi != EPI_FRO2 && a.A != a.B) ||
                       a.M != a.N || a.lda != a.ldb || (a.M & 3)))
+    return hipErrorInvalidValue;
+  // the matrix-writing epilogues address their arrays [M or N rows][ldc] through 32-bit byte offsets
+  if ((epi == EPI_F32 || epi == EPI_GRAMW || epi == EPI_SQUARE || epi == EPI_XLAST || epi == EPI_XOUT) &&
+      (a.ldc < a.N || (epi != EPI_F32 && a.ldc < a.M) || (int64_t)((a.M > a.N ? a.M : a.N) + 256) * a.ldc >= (1ll << 29)))
     return hipErrorInvalidValue;
   if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
