@@ -178,9 +178,10 @@ conqur_status conqur_quant_error_zp(conqur_ctx* ctx, const void* X_dev, uint64_t
  * fp32-equivalent products for fp32), stored in act_dtype -- Eq. 1's R x~ before
  * normalisation; with the rows of a weight matrix as X this folds the learned rotation
  * into that matrix (App. A).  X_dev as in conqur_step_batch (T <= max_tokens rows per
- * call).  Y_dev: DEVICE, T rows of y_row_stride_elems >= d elements of act_dtype, owned
- * by the caller, must not overlap X.  Asynchronous on the context's stream; does not
- * change the calibration state.
+ * call).  Y_dev: DEVICE, T rows of y_row_stride_elems elements of act_dtype
+ * (d <= y_row_stride_elems < 2^21, else CONQUR_EINVAL), owned by the caller, must not
+ * overlap X.  Asynchronous on the context's stream; does not change the calibration
+ * state.
  */
 conqur_status conqur_rotate(conqur_ctx* ctx, const void* X_dev, uint64_t T, uint64_t row_stride_elems, void* Y_dev,
                             uint64_t y_row_stride_elems);

@@ -1006,8 +1006,8 @@ conqur_status conqur_rotate(conqur_ctx* ctx, const void* X, uint64_t T64, uint64
   if (st != CONQUR_OK) return st;
   if (!Y) return fail(ctx, CONQUR_EINVAL, "Y_dev is NULL");
   const uint64_t esz = ctx->f32 ? 4 : 2;
-  if (y_stride64 < (uint64_t)ctx->d || y_stride64 >= (1ull << 40) || (reinterpret_cast<uintptr_t>(Y) % esz) != 0)
-    return fail(ctx, CONQUR_EINVAL, "Y row stride must be >= d and Y aligned to its element size");
+  if (y_stride64 < (uint64_t)ctx->d || y_stride64 >= (1ull << 21) || (reinterpret_cast<uintptr_t>(Y) % esz) != 0)
+    return fail(ctx, CONQUR_EINVAL, "Y row stride must be >= d and < 2^21, and Y aligned to its element size");
   HIP_TRY(hipSetDevice(ctx->cfg.device));
   const int64_t T = (int64_t)T64, stride = (int64_t)stride64;
   hipStream_t s = ctx->stream;

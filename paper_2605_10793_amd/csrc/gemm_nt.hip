@@ -333,23 +333,48 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
     __builtin_amdgcn_raw_buffer_store_b16((unsigned short)t.y, r, off + 2u * rb, 0, 0);
     __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(t.y >> 16), r, off + 3u * rb, 0, 0);
   };
+  // The accumulators as activations Y[m][n] (bf16 or fp32 by g.c_is_f32), row pitch `pitch`: the pitch is the caller's,
+  // so the offsets are taken relative to the tile's first row (at most BM rows x pitch x 4 bytes, which the launcher
+  // keeps below 2^31); rows past M lie beyond the range, columns past N are masked.
+  [[maybe_unused]] auto store_act = [&](void* base, int64_t pitch, int64_t batch_off) {
+    const uint32_t pu = (uint32_t)pitch;
+    const uint32_t rows = (uint32_t)(g.M - m0 < BM ? g.M - m0 : BM);
+    const uint32_t lane_el = (uint32_t)(wm * WM + 4 * half) * pu + (uint32_t)(nw + col);
+    const int64_t tile_el = (int64_t)bz * batch_off + (int64_t)m0 * pitch;
+    if (g.c_is_f32) {
+      const auto r = out_rsrc(reinterpret_cast<float*>(base) + tile_el, rows * pu * 4u);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const uint32_t o = n_ok[j] ? (lane_el + 32u * j) * 4u : kOobOffset;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) st32(r, o + (uint32_t)(32 * i + 8 * (e >> 2) + (e & 3)) * pu * 4u, acc[i][j][e]);
+        }
+    } else {
+      const auto r = out_rsrc(reinterpret_cast<bf16_bits*>(base) + tile_el, rows * pu * 2u);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const uint32_t o = n_ok[j] ? (lane_el + 32u * j) * 2u : kOobOffset;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            uint2 t;
+            t.x = f32x2_to_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+            t.y = f32x2_to_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            const uint32_t oq = o + (uint32_t)(32 * i + 8 * q) * pu * 2u, rb = 2u * pu;
+            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)t.x, r, oq, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(t.x >> 16), r, oq + rb, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)t.y, r, oq + 2u * rb, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(t.y >> 16), r, oq + 3u * rb, 0, 0);
+          }
+        }
+    }
+  };
 
   if constexpr (EPI == EPI_SIGN_ACT) {   // the rotated rows themselves, as EPI_ACT writes them
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m >= g.M) continue;
-          const int64_t off = (int64_t)bz * g.batchY + (int64_t)m * g.ldy + n;
-          if (g.c_is_f32) reinterpret_cast<float*>(g.Yact)[off] = acc[i][j][e];
-          else reinterpret_cast<bf16_bits*>(g.Yact)[off] = f32_to_bf16(acc[i][j][e]);
-        }
-      }
+    store_act(g.Yact, g.ldy, g.batchY);
   }
   if constexpr (EPI == EPI_SIGN || EPI == EPI_SIGN_ACT || EPI == EPI_SIGN_XT) {
     // St is the transpose of the accumulator tile.  Storing it straight from the registers gives every lane 8 bytes of
@@ -455,21 +480,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_nt_kernel(const GemmArgs 
       }
     }
   } else if constexpr (EPI == EPI_ACT) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + col;
-        if (n >= g.N) continue;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = mw + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (m >= g.M) continue;
-          const int64_t off = (int64_t)bz * g.batchC + (int64_t)m * g.ldc + n;
-          if (g.c_is_f32) reinterpret_cast<float*>(g.C)[off] = acc[i][j][e];
-          else reinterpret_cast<bf16_bits*>(g.C)[off] = f32_to_bf16(acc[i][j][e]);
-        }
-      }
+    store_act(g.C, g.ldc, g.batchC);
   } else if constexpr (EPI == EPI_F32) {
     const auto rC = out_rsrc(reinterpret_cast<float*>(g.C) + (int64_t)bz * g.batchC, nat_rows * 4u);
 #pragma unroll
@@ -830,6 +841,9 @@ hipError_t launch_gemm_nt(const GemmArgs& a, GemmEpilogue epi, int batch, hipStr
   // the matrix-writing epilogues address their arrays [M or N rows][ldc] through 32-bit byte offsets
   if ((epi == EPI_F32 || epi == EPI_GRAMW || epi == EPI_SQUARE || epi == EPI_XLAST || epi == EPI_XOUT) &&
       (a.ldc < a.N || (epi != EPI_F32 && a.ldc < a.M) || (int64_t)((a.M > a.N ? a.M : a.N) + 256) * a.ldc >= (1ll << 29)))
+    return hipErrorInvalidValue;
+  // EPI_ACT / EPI_SIGN_ACT address Y relative to a tile's first row: 256 rows x pitch x 4 bytes below 2^31
+  if ((epi == EPI_ACT && (a.ldc < a.N || a.ldc >= (1ll << 21))) || (epi == EPI_SIGN_ACT && (a.ldy < a.N || a.ldy >= (1ll << 21))))
     return hipErrorInvalidValue;
   if (epi == EPI_XLAST && (!a.C32 || !a.Pn || !a.Pt || (a.M & 3) || a.np_out < 1 || a.np_out > 2)) return hipErrorInvalidValue;
   switch (epi) {
