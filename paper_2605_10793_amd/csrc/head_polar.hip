@@ -7,12 +7,13 @@
 // path needs two GEMM launches per step, which at 128 x 128 are launch latency only.
 // Per step, with every product a 32x32x16 fp16 MFMA on K-contiguous operands (the iterate and the factor are held as
 // fp16: 11 significant bits at the rate of bf16's 8; every entry is at most a few units in magnitude):
-//   G = X^T X            A = B = X^T                     -> W = a I + b G, bf16, to LDS
-//   X' = X W             A = X,  B = W (symmetric)       -> accumulators hold X'   : packed stores give X'^T
-//   X'^T = W X^T         A = W,  B = X                   -> accumulators hold X'^T : packed stores give X'
-// (an accumulator lane owns 4 consecutive rows of one column, i.e. 8 contiguous bytes of the
-// transposed matrix: computing the product in both orientations replaces the scattered
-// 2-byte stores a single orientation would need for its own layout).
+//   G = X^T X            A = B = X^T                     -> W = a I + b G, fp16, to LDS
+//   X' = X W             A = X,  B = W (symmetric)       -> accumulators hold X'
+// An accumulator lane owns 4 consecutive rows of one column, i.e. 8 contiguous bytes of the transposed matrix:
+// X'^T goes to LDS as packed 8-byte writes, X' itself as four 2-byte writes per such group (64 per lane and step,
+// their addresses computed once).  Computing the product in the other orientation as well (X'^T = W X^T, packed
+// stores for both layouts) cost a third of the step's MFMA and LDS-read time and is kept for the last step only,
+// whose results leave for HBM.
 // The last step writes what the closing iterations read: the iterate rounded to bf16, as
 // fp32 and as one plane of each layout.
 #include "kernels.h"
@@ -94,6 +95,36 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
       }
   };
 
+  // LDS byte offsets of the natural-layout positions of this lane's accumulator elements in tile row i = 0
+  // (tile row 1 lies 32 rows = 32 * ROWB bytes further on): element e = 4 jj + ii of acc[.][j].
+  uint32_t nat_addr[2][4][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii) {
+        const int m = 64 * wm + 8 * jj + 4 * half + ii, n = 64 * wn + 32 * j + col;
+        nat_addr[j][jj][ii] = (uint32_t)(loff(m, n >> 3) + (n & 7) * 2);
+      }
+  // The iterate itself into an LDS operand: row m, K position n, one fp16 value at a time.
+  auto store_natural = [&](unsigned char* dst, const f32x16 (&acc)[2][2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const uint32_t lo = f32x2_to_f16x2(acc[i][j][4 * jj], acc[i][j][4 * jj + 1]);
+          const uint32_t hi = f32x2_to_f16x2(acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]);
+          unsigned char* d = dst + i * 32 * ROWB;
+          *reinterpret_cast<unsigned short*>(d + nat_addr[j][jj][0]) = (unsigned short)lo;
+          *reinterpret_cast<unsigned short*>(d + nat_addr[j][jj][1]) = (unsigned short)(lo >> 16);
+          *reinterpret_cast<unsigned short*>(d + nat_addr[j][jj][2]) = (unsigned short)hi;
+          *reinterpret_cast<unsigned short*>(d + nat_addr[j][jj][3]) = (unsigned short)(hi >> 16);
+        }
+  };
+
   f32x16 acc[2][2], accT[2][2];
   for (int k = 0; k < sched.nsteps; ++k) {
     const bool last = k + 1 == sched.nsteps;
@@ -102,11 +133,13 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
     store_transposed(sW, 64 * wm, 64 * wn, acc, sched.a[k], sched.b[k]);
     __syncthreads();
     product(sXn, 64 * wm, sW, 64 * wn, acc);    // X'   [r][c]
-    product(sW, 64 * wm, sXn, 64 * wn, accT);   // X'^T [c][r]
-    if (last) break;
+    if (last) {
+      product(sW, 64 * wm, sXn, 64 * wn, accT);   // X'^T [c][r]: the natural-layout plane below as packed stores
+      break;
+    }
     __syncthreads();                            // every wavefront has read the old iterate
     store_transposed(sXt, 64 * wm, 64 * wn, acc, 0.0f, 1.0f);
-    store_transposed(sXn, 64 * wm, 64 * wn, accT, 0.0f, 1.0f);
+    store_natural(sXn, acc);
     __syncthreads();
   }
 

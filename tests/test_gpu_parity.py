@@ -765,6 +765,10 @@ def test_error_paths(B):
         assert e.value.status == B.EINVAL
         with pytest.raises(ValueError):
             cal.rotate(X[:8], torch.zeros(8, 32, dtype=torch.bfloat16, device="cuda:0"))   # output narrower than d
+        Y1 = torch.zeros(1, 64, dtype=torch.bfloat16, device="cuda:0")
+        with pytest.raises(B.ConqurError) as e:                                     # output row pitch of 2^21 elements or more
+            cal._check(B.load().conqur_rotate(cal._h, X.data_ptr(), 1, 64, Y1.data_ptr(), 1 << 21))
+        assert e.value.status == B.EINVAL
         with pytest.raises(B.ConqurError) as e:
             cal.last_corners(8)                                                     # no step yet
         assert e.value.status == B.ESTATE
