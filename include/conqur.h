@@ -58,7 +58,7 @@ typedef struct {
                                (that ties R to R_prev on the null space of M, where every completion is
                                optimal, and breaks exact degeneracies a polynomial iteration would keep;
                                it moves <R, M> by less than 1e-6 relative)                            */
-  float polar_tol;          /* stop when ||X^T X - I||_F <= tol; 0 selects 8e-5                      */
+  float polar_tol;          /* stop when ||X^T X - I||_F <= tol; 0 selects 9.5e-5                    */
   uint32_t polar_max_iters; /* 0 selects 200                                                        */
   uint32_t polar_precision; /* arithmetic of the main polar iterations: 0 = single fp16 operands (fast; 11
                                significant bits: meets the orthogonality and objective tolerances, R itself

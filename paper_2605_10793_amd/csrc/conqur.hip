@@ -221,7 +221,9 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
   conqur_ctx* ctx = new (std::nothrow) conqur_ctx();
   if (!ctx) return CONQUR_ENOMEM;
   ctx->cfg = *cfg;
-  if (ctx->cfg.polar_tol == 0.0f) ctx->cfg.polar_tol = 8e-5f;
+  // 9.5e-5: below the 1e-4 the update must end at, above the 8.4e-5 the orthogonality bound certifies at dh = 8192
+  // (its fp32 rounding term alone is 1e-8 dh), so that the largest width does not fall back to measuring every time
+  if (ctx->cfg.polar_tol == 0.0f) ctx->cfg.polar_tol = 9.5e-5f;
   if (ctx->cfg.polar_max_iters == 0) ctx->cfg.polar_max_iters = 200;
   ctx->d = (int)cfg->d; ctx->heads = (int)cfg->heads; ctx->dh = (int)dh;
   ctx->f32 = cfg->act_dtype == CONQUR_F32;
