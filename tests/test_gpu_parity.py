@@ -630,6 +630,15 @@ def test_rows_with_a_pitch_wider_than_d(B, d, heads, dtype):
         so, eo, _, _ = oc.quant_error(X, 4)
         sg, eg = cal.quant_error(view, 4)
         assert abs(sg - so) <= TOL_REL * so and abs(eg - eo) <= TOL_REL * eo
+        # the rotated rows into a buffer with a pitch of its own: every element against the oracle's, padding untouched
+        Ywide = torch.full((T, d + 40), 3.0, dtype=wide.dtype, device="cuda:0")
+        cal.rotate(view, Ywide[:, 8:8 + d])
+        torch.cuda.synchronize()
+        Yg = Ywide.float().cpu().numpy()
+        Yo = oc.rotate(X)
+        scale = np.abs(Yo).max()
+        assert np.max(np.abs(Yg[:, 8:8 + d] - Yo)) <= (2.0 ** -7 if dtype == "bf16" else 1e-5) * scale
+        assert np.all(Yg[:, :8] == 3.0) and np.all(Yg[:, 8 + d:] == 3.0)
     finally:
         cal.close()
 
