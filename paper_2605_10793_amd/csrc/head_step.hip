@@ -46,7 +46,7 @@ __global__ void __launch_bounds__(NTHREADS) k_head_step128(const bf16_bits* __re
   unsigned char* const sXt = sX + TT * XROW;             // x^ transposed (fp16): row channel, K = token
   unsigned char* const sCt = sXt + DH * TROW;            // corner signs transposed (fp16): row n, K = token
   __shared__ float sW[2][TT];      // kXhatScale / ||x|| per token of the tile (0: skipped), by tile parity
-  __shared__ double shd[16];
+  __shared__ double shd[3][16];
 
   const int h = blockIdx.x, sp = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -220,20 +220,11 @@ __global__ void __launch_bounds__(NTHREADS) k_head_step128(const bf16_bits* __re
   {
     double r = (double)n_rows, k = (double)n_skipped;
     l_acc = wave_sum_d(l_acc); r = wave_sum_d(r); k = wave_sum_d(k);
+    if (lane == 0) { shd[0][wave] = l_acc; shd[1][wave] = r; shd[2][wave] = k; }
     __syncthreads();
-    if (lane == 0) shd[wave] = l_acc;
-    __syncthreads();
-    auto total = [&]() { double t = 0.0; for (int i = 0; i < NTHREADS / 64; ++i) t += shd[i]; return t; };
-    const double lt = total();
-    __syncthreads();
-    if (lane == 0) shd[wave] = r;
-    __syncthreads();
-    const double rt = total();
-    __syncthreads();
-    if (lane == 0) shd[wave] = k;
-    __syncthreads();
-    const double kt = total();
     if (tid == 0) {
+      double lt = 0.0, rt = 0.0, kt = 0.0;
+      for (int i = 0; i < NTHREADS / 64; ++i) { lt += shd[0][i]; rt += shd[1][i]; kt += shd[2][i]; }
       atomicAdd(L + h, lt);
       atomicAdd(rows + h, (unsigned long long)rt);
       atomicAdd(skipped + h, (unsigned long long)kt);
