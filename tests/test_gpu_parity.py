@@ -134,7 +134,17 @@ def compare_quant(B, cal, oc, X, w, tag):
     # per-row diagnostics (participation ratio, range ratio)
     pr_o, rho_o = oc.row_diagnostics(X)
     pr_g, rho_g = cal.row_diagnostics(Xd)
-    assert np.allclose(pr_g, pr_o, rtol=1e-3, atol=1e-7) and np.allclose(rho_g, rho_o, rtol=1e-3, atol=1e-7), tag
+    if w.dtype == "bf16":
+        # Y is stored in bf16 before it is scored; where the two sides' fp32 / fp64 sums fall on either side of a rounding
+        # boundary an entry differs by one bf16 ulp (up to 2^-7 relative, see the element-wise bound above), and if it is
+        # the row's extreme entry rho = max^2 / ||y||^2 of that row moves by up to twice that.  Such rows are rare
+        # (fewer than 2 % of the entries differ at all): all rows within two ulps of the extreme, nearly all within 1e-3.
+        for got, want in ((pr_g, pr_o), (rho_g, rho_o)):
+            rel = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
+            ok = (rel <= 1e-3) | (np.abs(got - want) <= 1e-7)
+            assert rel[~ok].max(initial=0.0) <= 2.0 ** -6 and (~ok).sum() <= max(1, len(rel) // 50), (tag, rel.max(), int((~ok).sum()))
+    else:
+        assert np.allclose(pr_g, pr_o, rtol=1e-3, atol=1e-7) and np.allclose(rho_g, rho_o, rtol=1e-3, atol=1e-7), tag
     # the zero-point quantiser, at the appendix's definition and at the evaluation clipping ratio
     for clip in (1.0, 0.9):
         so, eo, _, _ = oc.quant_error_zp(X, 4, clip)
