@@ -217,6 +217,26 @@ def test_small_streams(B, d, T, heads, dtype, lam):
     run_stream(B, w, 2, check_R=lam > 0)
 
 
+def test_random_shapes(B):
+    """Widths, head counts and token counts drawn at random within the documented limits (dh a multiple of 16), one batch
+    and one update each through every comparison of run_stream: ragged tiles in every dimension of every kernel, the
+    fused per-head path (dh = 128) included."""
+    import random
+    rng = random.Random(20251)
+    for it in range(24):
+        heads = rng.choice([1, 1, 1, 2, 3, 5])
+        dh = 128 if it % 6 == 5 else (16 * rng.randint(1, 40) if heads > 1 else 16 * rng.randint(1, 56))
+        d = dh * heads
+        T = rng.choice([1, 3, 17, 64, 65, 127, 200, 333, 511, 700])
+        dtype = rng.choice(["bf16", "bf16", "f32"]) if d <= 512 and dh != 128 else "bf16"
+        lam = rng.choice([0.0, 0.1, 0.5])
+        if d * T < 4096:
+            T = 200    # the emitted-rows check of compare_quant averages the levels' rounding over the entries
+        w = I.small_workload(d, T, n_batches=1, heads=heads, dtype=dtype, seed=5000 + it, prox_lambda=lam, massive_frac=0.01)
+        say(f"random shape {it}: d={d} heads={heads} T={T} {dtype} lambda={lam}")
+        run_stream(B, w, 1, check_R=False)
+
+
 @pytest.mark.parametrize("precision,verify", [(0, 1), (1, 0), (2, 1)])
 def test_polar_options(B, precision, verify):
     """The other arithmetic modes of the update (two / three operand planes in the main phase) and the measured
