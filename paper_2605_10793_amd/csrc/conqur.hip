@@ -736,6 +736,9 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // on the null space of M, halved.  (Smaller ones still grow by the factor a > 2.5 per
   // step and are finished by the closing iterations.)
   int handover_planes = 0;   // 1 / 2: the iterate in PX is exactly the sum of that many planes of buffer `cur`; 0: all three
+  bool allow_fuse = true;    // (only the first main phase of an update: not the one after a nudge)
+  int fused_slot = -1;       // heads of width 128: the launch of the main phase also took the closing step (per head, if
+                             // its residual allowed); residual slots fused_slot (||I - G||_F^2) and fused_slot + 1 (||D^2||_F^2)
   auto main_phase = [&](double l0, bool planes_ready) -> conqur_status {
     if (!planes_ready) HIP_TRY(launch_pack(ctx->PX, h, dh, dh, np_main, ctx->PXn[cur], ctx->PXt[cur], plane, s, main_f16));
     const double e_stop = np_main == 1 ? 4e-3 : 5e-4;   // the safety margins below floor the ripple near 2e-4
@@ -754,7 +757,21 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
         l = 0.98 * (1.0 - E);
         u = 1.01 * (1.0 + E);
       }
-      HIP_TRY(launch_head_polar128(ctx->PXn[cur], ctx->PXt[cur], h, sc, ctx->PX, ctx->PXn[cur ^ 1], ctx->PXt[cur ^ 1], s));
+      // With the bound instead of a measurement at the end (the default) the closing step rides in the same launch:
+      // every head whose residual allows the quintic form takes it and leaves R, the rotate operand and <R, M>.
+      HeadPolarClose hc;
+      const bool fuse = allow_fuse && !ctx->cfg.polar_verify && iters + sc.nsteps + 1 <= cap && slot + 2 < kResidSlots - 8;
+      if (fuse) {
+        hc.R = ctx->R; hc.RopT = ctx->RopT; hc.M = ctx->M;
+        hc.res_out = ctx->resid + (size_t)slot * h; hc.sq_out = ctx->resid + (size_t)(slot + 1) * h; hc.inner_out = ctx->inner;
+        hc.res_max = (float)(1e-2 * std::sqrt((double)dh));
+        fused_slot = slot;
+        slot += 2;
+      } else {
+        fused_slot = -1;
+      }
+      HIP_TRY(launch_head_polar128(ctx->PXn[cur], ctx->PXt[cur], h, sc, ctx->PX, ctx->PXn[cur ^ 1], ctx->PXt[cur ^ 1],
+                                   fuse ? &hc : nullptr, s));
       cur ^= 1;
       handover_planes = 1;
       iters += sc.nsteps;
@@ -789,6 +806,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   const double lam_eff = std::max((double)ctx->cfg.prox_lambda, 9.5367431640625e-07);
   conqur_status st = main_phase(0.5 * lam_eff / ((1.0 + lam_eff) * std::sqrt((double)dh)), true);
   if (st != CONQUR_OK) return st;
+  allow_fuse = false;
 
   // ---- closing iterations, Gram matrix in fp32-equivalent arithmetic (3 planes, 6 products).
   // With D = (I - X^T X)/2 the Newton-Schulz steps are X <- X + X D (cubic) and
@@ -811,7 +829,47 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
     return CONQUR_OK;
   };
-  while (true) {
+  // Outcome of a closing step taken inside the main phase's launch (heads of width 128): accepted if every head took it
+  // and the bound from ||D^2||_F (see below) is within the tolerance; otherwise the general closing steps continue from
+  // the hand-over state, which that launch wrote as well.  (R of the heads that did take the step is overwritten already:
+  // should the rare nudge below follow, it moves those heads towards their new rotation instead of the previous one.)
+  auto fused_outcome = [&]() -> conqur_status {
+    HIP_TRY(hipMemcpyAsync(hist + (size_t)fused_slot * h, ctx->resid + (size_t)fused_slot * h, 2 * h * sizeof(double),
+                           hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipEventRecord(ctx->ev_resid, s));
+    // expected to be the end: what follows the last step goes in before the host waits
+    HIP_TRY(launch_fill_zero(ctx->L, ctx->stat_words * sizeof(double), s));
+    if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][1], s));
+    HIP_TRY(hipEventSynchronize(ctx->ev_resid));
+    bool ok = true;
+    double worst_res = 0.0, worst_pred = 0.0;
+    for (int q = 0; q < h; ++q) {
+      const double r2 = hist[(size_t)fused_slot * h + q], s2 = hist[(size_t)(fused_slot + 1) * h + q];
+      if (!std::isfinite(r2)) return fail(ctx, CONQUR_ENONFINITE, "update_rotation: non-finite polar iterate");
+      worst_res = std::max(worst_res, std::sqrt(r2));
+      if (!(s2 >= 0.0)) { ok = false; continue; }
+      const double b = kCubeFactor * std::pow(std::sqrt(s2), 1.5) + kOrthFloorPerDim * dh;
+      worst_pred = std::max(worst_pred, b);
+      if (!(std::isfinite(b) && b <= tol)) ok = false;
+    }
+    if (trace) std::fprintf(stderr, "[conqur] polar closing in the main phase's launch: resid_F=%.6e bound on resid_F=%.4e accepted=%d\n",
+                            worst_res, worst_pred, (int)ok);
+    if (!ok) { fused_slot = -1; return CONQUR_OK; }
+    for (int q = 0; q < h; ++q) {
+      const double b = kCubeFactor * std::pow(std::sqrt(hist[(size_t)(fused_slot + 1) * h + q]), 1.5) + kOrthFloorPerDim * dh;
+      hist[(size_t)(fused_slot + 1) * h + q] = b * b;
+    }
+    last_slot = fused_slot + 1;
+    ++iters; ++closing;
+    converged = predicted = finished = true;
+    final_x = ctx->R;
+    return CONQUR_OK;
+  };
+  if (fused_slot >= 0) {
+    st = fused_outcome();
+    if (st != CONQUR_OK) return st;
+  }
+  while (!converged) {
     HIP_TRY(gram(handover_planes == 1 ? kSeg1 : (handover_planes == 2 ? kSeg4 : kSeg6), 0.5f, -0.5f, 2, true));
     const SegList& seg_corr = handover_planes == 1 ? kSeg2 : kSeg3;   // the correction product X (D + 1.5 D^2)
     handover_planes = 0;   // whatever follows (correction step, nudge) writes all three planes again

@@ -82,8 +82,21 @@ struct PolarSchedule {
   int nsteps;
   float a[kPolarScheduleMax], b[kPolarScheduleMax];
 };
+// close non-null: each head whose residual ||I - X^T X||_F at the hand-over is at most res_max also takes the closing
+// step X <- X + X (D + 1.5 D^2), D = (I - X^T X)/2, in the same launch and writes R (fp32), RopT (bf16 plane of R^T) and
+// inner_out[h] = <R, M>; res_out[h] = ||I - X^T X||_F^2 at the hand-over, sq_out[h] = ||D^2||_F^2, or < 0 if the head did
+// not take the step (then R, RopT and inner_out of that head are untouched).  The hand-over outputs are written either way.
+struct HeadPolarClose {
+  float* R;
+  bf16_bits* RopT;
+  const float* M;
+  double* res_out;
+  double* sq_out;
+  double* inner_out;
+  float res_max;
+};
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
-                                bf16_bits* Pn, bf16_bits* Pt, hipStream_t s);
+                                bf16_bits* Pn, bf16_bits* Pt, const HeadPolarClose* close, hipStream_t s);
 
 // Per-row fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse / row_en, then their sums over rows:
 // out[0] = SSE, out[1] = energy (skipped if out is null).  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
