@@ -101,6 +101,7 @@ def run_workload(B, I, w, T, K, W, full, lam_zero_updates):
     torch.cuda.synchronize()
     whole = {k: 0.0 for k in ("step", "quant", "update")}
     iters = 0
+    issued = 0.0
     rel = []
     t0 = time.perf_counter()
     for i in range(W, W + K):
@@ -109,6 +110,7 @@ def run_workload(B, I, w, T, K, W, full, lam_zero_updates):
         for k in whole:
             whole[k] += tm[k]
         iters += st[0]["iters"]
+        issued += st[0]["mfma_flop"]
         rel.append(r)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -139,6 +141,8 @@ def run_workload(B, I, w, T, K, W, full, lam_zero_updates):
         step_flops=step_flops, gemm_ms=gemm_ms, polar_flops=polar_flops, y_bytes=y_bytes,
         step_frac=step_flops / (step_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         polar_frac=polar_flops / (whole["update"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        polar_flops_issued=issued / K,
+        polar_frac_issued=(issued / K) / (whole["update"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
     )
     if w.dh == 128 and w.dtype == "bf16":
         # heads of width 128 take the fused step kernel: bound by reading X once (256 bytes per token and head)
@@ -264,9 +268,12 @@ def main():
         "roofline_polar": {
             "bound": "mfma", "achieved": r["polar_flops"] / (r["ms_per_procrustes"] * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": r["polar_frac"],
-            "note": "algorithmic 4*d^3 per polar iteration (one Gram matrix, one apply) over the whole update; the "
-                    "MFMA work actually issued differs: symmetric products run on the tiles on and above the "
-                    "diagonal only, the closing step adds the D^2, ||D^3|| and two-plane correction products",
+            "issued": {"achieved": r["polar_flops_issued"] / (r["ms_per_procrustes"] * 1e-3) / 1e12, "frac": r["polar_frac_issued"],
+                       "flop_per_update": r["polar_flops_issued"]},
+            "note": "achieved / frac: algorithmic 4*d^3 per polar iteration (one Gram matrix, one apply) over the whole "
+                    "update; issued: the MFMA work the update's launches really ran, as the library counts it "
+                    "(conqur_update_stats.mfma_flop: symmetric products run on the tiles on and above the diagonal only, "
+                    "the closing step adds the D^2 and two-plane correction products)",
         },
         "roofline_quant_error": {
             "bound": "hbm", "achieved": r["y_bytes"] / (acc["quant_error"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
@@ -315,6 +322,7 @@ def main():
                                  "unit": "TFLOP/s", "frac": ro["step_frac"],
                                  "note": "whole conqur_step_batch, 4 dh^2 heads FLOP per token"}
             e["roofline_polar_frac"] = ro["polar_frac"]
+            e["roofline_polar_frac_issued"] = ro["polar_frac_issued"]
             if "lam0" in ro:
                 e["procrustes_lambda_to_zero"] = ro["lam0"]
             others.append(e)

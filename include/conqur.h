@@ -95,6 +95,11 @@ typedef struct {
   uint32_t orth_measured; /* 1: orth_err was measured; 0: it is the estimate                          */
   uint32_t reserved;
   double l1;            /* L of the rows this update consumed (as conqur_batch_stats.l1 just before it)   */
+  double mfma_flop;     /* multiply-add work the update's matrix products issued, in FLOP, all heads
+                           together (tiles that ran x tile area x contraction length x 2: symmetric
+                           products run on the tiles on and above the diagonal only, split-plane
+                           products count once per plane pair); the algorithmic figure is
+                           4 dh^3 heads per iteration                                                 */
 } conqur_update_stats;
 
 /*

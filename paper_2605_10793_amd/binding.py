@@ -42,7 +42,8 @@ class BatchStats(ctypes.Structure):
 class UpdateStats(ctypes.Structure):
     _fields_ = [("iters", ctypes.c_uint32), ("accurate", ctypes.c_uint32), ("orth_err", ctypes.c_double),
                 ("inner", ctypes.c_double), ("m_fro", ctypes.c_double), ("ms", ctypes.c_double),
-                ("orth_measured", ctypes.c_uint32), ("reserved", ctypes.c_uint32), ("l1", ctypes.c_double)]
+                ("orth_measured", ctypes.c_uint32), ("reserved", ctypes.c_uint32), ("l1", ctypes.c_double),
+                ("mfma_flop", ctypes.c_double)]
 
 
 class ConqurError(RuntimeError):
@@ -197,7 +198,7 @@ class Calibrator:
         st = self._check(self._lib.conqur_update_rotation(self._h, arr), allow)
         return st, [dict(iters=int(a.iters), accurate=int(a.accurate), orth_err=float(a.orth_err),
                          inner=float(a.inner), m_fro=float(a.m_fro), ms=float(a.ms),
-                         orth_measured=bool(a.orth_measured), l1=float(a.l1)) for a in arr]
+                         orth_measured=bool(a.orth_measured), l1=float(a.l1), mfma_flop=float(a.mfma_flop)) for a in arr]
 
     def quant_error(self, X, bits: int = 4) -> Tuple[float, float]:
         p, T, stride = self._x(X)

@@ -632,6 +632,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   if (ctx->head_fused) HIP_TRY(hipMemcpyAsync(ctx->ldot, ctx->L, h * sizeof(double), hipMemcpyDeviceToDevice, s));
   int slot = 0;           // next residual-history slot
   uint32_t iters = 0, closing = 0;
+  double mfma_flop = 0.0; // multiply-add work the products of this update issue (reported in the statistics)
 
   auto gram = [&](const SegList& sl, float ci, float cg, int np_w, bool want_resid, int f16 = 0) -> hipError_t {
     GemmArgs g;
@@ -645,6 +646,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.symmetric = 1;   // X^T X: tiles above the diagonal are computed once and stored twice
     g.resid_part = want_resid ? ctx->resid_part : nullptr; g.coef_i = ci; g.coef_g = cg;
     hipError_t e = launch_gemm_nt(g, EPI_GRAMW, h, s);
+    mfma_flop += gemm_issued_flop(g, EPI_GRAMW, h);
     if (e == hipSuccess && want_resid)
       e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);
     return e;
@@ -667,11 +669,13 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       g.C32 = ctx->PX;
       g.np_out = -np_t;
       e = launch_gemm_nt(g, EPI_XLAST, h, s);
+      mfma_flop += gemm_issued_flop(g, EPI_XLAST, h);
     } else {
       g.np_out = np_t; g.np_out_n = np_n;
       g.Xadd = add_x ? ctx->PX : nullptr;
       g.C32 = out32;
       e = launch_gemm_nt(g, EPI_XOUT, h, s);
+      mfma_flop += gemm_issued_flop(g, EPI_XOUT, h);
     }
     cur ^= 1;
     return e;
@@ -690,6 +694,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.Padd = ctx->PW; g.np_add = 2; g.coef_i = 0.0f; g.coef_g = 1.5f;
     g.symmetric = 1;
     sq_slot = -1;
+    mfma_flop += gemm_issued_flop(g, EPI_SQUARE, h);
     if (!keep_square) return launch_gemm_nt(g, EPI_GRAMW, h, s);
     g.Pacc = ctx->PW2 + 2 * plane;   // D^2 itself, third plane of the buffer
     g.resid_part = ctx->resid_part;
@@ -713,6 +718,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
     g.symmetric = 1;   // D and D^2 commute: D^3 is symmetric (up to the planes' rounding, which this estimate absorbs)
     g.resid_part = ctx->resid_part;
     hipError_t e = launch_gemm_nt(g, EPI_FRO2, h, s);
+    mfma_flop += gemm_issued_flop(g, EPI_FRO2, h);
     if (e == hipSuccess) e = launch_sum_partials(ctx->resid_part, ctx->resid_parts, h, ctx->resid + (size_t)slot * h, s);
     return e;
   };
@@ -775,6 +781,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       cur ^= 1;
       handover_planes = 1;
       iters += sc.nsteps;
+      // per head: two 128^3 products per step, a third in the last one, and four in the closing step if it is taken
+      mfma_flop += 2.0 * 128.0 * 128.0 * 128.0 * h * (2.0 * sc.nsteps + 1.0 + (fuse ? 4.0 : 0.0));
       if (trace) std::fprintf(stderr, "[conqur] polar main phase: %d steps in one launch, l0=%.3e\n", sc.nsteps, l0);
       return CONQUR_OK;
     }
@@ -999,6 +1007,7 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
       out[q].orth_err = std::sqrt(hist[(size_t)last_slot * h + q]);
       out[q].inner = inner[q]; out[q].m_fro = std::sqrt(fro2[q]); out[q].ms = ms;
       out[q].l1 = ctx->head_fused ? ldot[q] : ctx->l_base[q] + std::sqrt((double)dh) * ldot[q];
+      out[q].mfma_flop = mfma_flop;
     }
   }
   ctx->l_base.assign(h, 0.0);

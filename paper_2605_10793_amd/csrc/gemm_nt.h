@@ -89,6 +89,10 @@ struct GemmArgs {
 // Enqueue the GEMM on `stream`.  Returns hipSuccess or the launch error.
 hipError_t launch_gemm_nt(const GemmArgs& args, GemmEpilogue epi, int batch, hipStream_t stream);
 
+// Multiply-add work launch_gemm_nt issues for these arguments, in FLOP: workgroups that run x tile area x K x segments
+// x 2 (a symmetric launch runs the tiles on and above the diagonal only).
+double gemm_issued_flop(const GemmArgs& args, GemmEpilogue epi, int batch);
+
 // Number of workgroups launch_gemm_nt uses for an M x N problem with `batch` entries (size of the clock probe / 4).
 int gemm_num_workgroups(int M, int N, int batch);
 

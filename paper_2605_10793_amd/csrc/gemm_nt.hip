@@ -824,6 +824,19 @@ int gemm_num_partials(int M, int N, int batch, int symmetric) {
   return ((M + u.bm - 1) / u.bm) * ((N + u.bn - 1) / u.bn) * u.wgm * u.wgn;
 }
 
+double gemm_issued_flop(const GemmArgs& a, GemmEpilogue epi, int batch) {
+  int t = pick_tile(a.M, a.N, batch);
+  bool sym = false;
+  if (a.symmetric && (epi == EPI_GRAMW || epi == EPI_SQUARE || epi == EPI_FRO2)) {
+    const int ts = pick_tile_sym(a.M, batch);
+    if (ts >= 0) { t = ts; sym = true; }
+  }
+  const Tile& u = kTiles[t];
+  const int64_t tm = (a.M + u.bm - 1) / u.bm, tn = (a.N + u.bn - 1) / u.bn;
+  const int64_t tiles = sym ? tm * (tm + 1) / 2 : tm * tn;
+  return 2.0 * (double)tiles * u.bm * u.bn * (double)a.K * a.nseg * batch;
+}
+
 int gemm_num_workgroups(int M, int N, int batch) {
   const Tile& t = kTiles[pick_tile(M, N, batch)];
   return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;

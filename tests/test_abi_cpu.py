@@ -43,7 +43,7 @@ def test_stats_structs_match_header_field_order():
         body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
         fields = re.findall(r"\b(?:uint64_t|uint32_t|double)\s+([a-z_0-9]+);", body)
         assert fields == [f[0] for f in cls._fields_], cname
-    assert ctypes.sizeof(binding.BatchStats) == 32 and ctypes.sizeof(binding.UpdateStats) == 56
+    assert ctypes.sizeof(binding.BatchStats) == 32 and ctypes.sizeof(binding.UpdateStats) == 64
 
 
 def test_binding_holds_no_method_arithmetic():

@@ -102,6 +102,10 @@ def compare_update(B, cal, oc, w, tag, check_R):
         assert abs(got - best) <= TOL_REL * abs(best), (tag, h, got, best)
         assert abs(st_g[h]["inner"] - inner_g) <= 1e-4 * abs(inner_g) + 1e-6
         assert abs(st_g[h]["m_fro"] - np.linalg.norm(M[h])) <= 1e-5 * np.linalg.norm(M[h])
+        # the multiply-add work the update reports as issued: of the order of the algorithmic 4 dh^3 per iteration and head
+        # (below it where symmetric products run half their tiles, above it for padded tiles and split-plane products)
+        algorithmic = 4.0 * w.dh ** 3 * w.heads * st_g[h]["iters"]
+        assert 0.5 * algorithmic <= st_g[h]["mfma_flop"] <= 16.0 * algorithmic, (tag, st_g[h]["mfma_flop"], algorithmic)
         if check_R:
             dR = np.abs(Rg[h] - oc.R[h]).max()
             say(f"  {tag} head {h}: max|R - R_oracle| = {dR:.2e}")
