@@ -15,7 +15,9 @@
 // stores for both layouts) cost a third of the step's MFMA and LDS-read time and is kept for the last step only,
 // whose results leave for HBM.
 // The last step writes what the closing iterations read: the iterate rounded to bf16, as
-// fp32 and as one plane of each layout.
+// fp32 and as one plane of each layout.  On request the same launch then takes the closing
+// step itself (exact Gram matrix of that bf16 iterate, D, D^2, two-plane correction; bf16
+// MFMAs) and leaves the rotation, the rotate operand and <R, M>: see HeadPolarClose.
 #include "kernels.h"
 
 namespace conqur {

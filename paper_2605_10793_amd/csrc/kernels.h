@@ -73,10 +73,10 @@ constexpr int kHeadReduceParts = 16;
 hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, double* fro2_part, hipStream_t s);
 
 // Main phase of the polar iteration for heads of width 128 in one launch (head_polar.hip): runs the composed cubics
-// X <- X (a_k I + b_k X^T X), k < nsteps, on single bf16 operand planes held in LDS.  Xn0 / Xt0: the start iterate as
-// one natural and one transposed bf16 plane [heads][128][128].  Outputs, as the last step of the general path writes them:
-// the result rounded to bf16, as X32 (fp32), Pt (one transposed plane) and Pn (one natural plane).
-// The start planes hold fp16 (the steps run on fp16 operands, 11 significant bits); the outputs are bf16.
+// X <- X (a_k I + b_k X^T X), k < nsteps, on single fp16 operand planes held in LDS (11 significant bits).  Xn0 / Xt0:
+// the start iterate as one natural and one transposed fp16 plane [heads][128][128].  Outputs, as the last step of the
+// general path writes them: the result rounded to bf16, as X32 (fp32), Pt (one transposed bf16 plane) and Pn (one
+// natural bf16 plane).
 constexpr int kPolarScheduleMax = 64;
 struct PolarSchedule {
   int nsteps;
