@@ -604,15 +604,25 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   const bool trace = std::getenv("CONQUR_TRACE") != nullptr;
   if (timed) HIP_TRY(hipEventRecord(ctx->ev[ST_UPDATE][0], s));
 
+  const int np_main = 1 + (int)ctx->cfg.polar_precision;
+  // Heads of width 128 on the fused path: the launch that runs the main phase also forms the start iterate (and, below,
+  // takes the closing step), so the update is the reduction of the token shares and that one launch.
+  HeadPolarStart hstart;
+  bool use_hstart = ctx->head_fused && dh == 128 && np_main == 1 && ctx->cfg.polar_max_iters > 0;
   if (ctx->parts_pending) {   // per-head step: M is summed from the token shares here, ||M||_F^2 from the same pass
     HIP_TRY(launch_head_reduce(ctx->Mpart, ctx->parts_pending, h, ctx->M, 0, ctx->dotrm_part, s));
-    HIP_TRY(launch_sum_partials(ctx->dotrm_part, kHeadReduceParts, h, ctx->fro2, s));
+    if (use_hstart) { hstart.fro2_parts = ctx->dotrm_part; hstart.nparts = kHeadReduceParts; }
+    else HIP_TRY(launch_sum_partials(ctx->dotrm_part, kHeadReduceParts, h, ctx->fro2, s));
     ctx->parts_pending = 0;
   } else {
     HIP_TRY(launch_fro2(ctx->M, h, blk, ctx->dotrm_part, ctx->fro2, s));
+    if (use_hstart) { hstart.fro2_parts = ctx->fro2; hstart.nparts = 1; }
+  }
+  if (use_hstart) {
+    hstart.M = ctx->M; hstart.R = ctx->R; hstart.fro2_out = ctx->fro2; hstart.lambda = ctx->cfg.prox_lambda;
+    hstart.L = ctx->L; hstart.ldot = ctx->ldot;
   }
 
-  const int np_main = 1 + (int)ctx->cfg.polar_precision;
   // Single-plane main steps run on fp16 operands (iterate and polynomial factor): the MFMA rate of bf16 with 11
   // instead of 8 significant bits, so that the rounding of a step, which the weak singular directions amplify by
   // 1/sigma, is 8 times smaller.  Every entry is at most a few units in magnitude: no range problem.  The
@@ -626,10 +636,12 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
   // planes of the first step (no fp32 copy: at least one main step runs, and the last one writes the fp32 iterate)
   // The same pass evaluates the l1 term of the rows this update consumes (general path; the fused per-head step
   // keeps it as it goes): a copy of either is taken here, before the statistics are cleared.
-  HIP_TRY(launch_polar_start_pack(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, np_main, nullptr,
-                                  ctx->PXn[cur], ctx->PXt[cur], plane, ctx->f32 ? 0 : 1,
-                                  ctx->head_fused ? nullptr : ctx->dot_part, ctx->ldot, s, main_f16));
-  if (ctx->head_fused) HIP_TRY(hipMemcpyAsync(ctx->ldot, ctx->L, h * sizeof(double), hipMemcpyDeviceToDevice, s));
+  if (!use_hstart) {
+    HIP_TRY(launch_polar_start_pack(ctx->M, ctx->R, h, dh, ctx->cfg.prox_lambda, ctx->fro2, np_main, nullptr,
+                                    ctx->PXn[cur], ctx->PXt[cur], plane, ctx->f32 ? 0 : 1,
+                                    ctx->head_fused ? nullptr : ctx->dot_part, ctx->ldot, s, main_f16));
+    if (ctx->head_fused) HIP_TRY(hipMemcpyAsync(ctx->ldot, ctx->L, h * sizeof(double), hipMemcpyDeviceToDevice, s));
+  }
   int slot = 0;           // next residual-history slot
   uint32_t iters = 0, closing = 0;
   double mfma_flop = 0.0; // multiply-add work the products of this update issue (reported in the statistics)
@@ -777,7 +789,8 @@ conqur_status conqur_update_rotation(conqur_ctx* ctx, conqur_update_stats* out) 
         fused_slot = -1;
       }
       HIP_TRY(launch_head_polar128(ctx->PXn[cur], ctx->PXt[cur], h, sc, ctx->PX, ctx->PXn[cur ^ 1], ctx->PXt[cur ^ 1],
-                                   fuse ? &hc : nullptr, s));
+                                   fuse ? &hc : nullptr, (use_hstart && planes_ready) ? &hstart : nullptr, s));
+      use_hstart = false;
       cur ^= 1;
       handover_planes = 1;
       iters += sc.nsteps;

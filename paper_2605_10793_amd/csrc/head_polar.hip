@@ -35,7 +35,7 @@ template <bool CLOSE>
 __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restrict__ Xn0, const bf16_bits* __restrict__ Xt0,
                                                        const PolarSchedule sched, float* __restrict__ X32,
                                                        bf16_bits* __restrict__ Pn, bf16_bits* __restrict__ Pt,
-                                                       const HeadPolarClose cl) {
+                                                       const HeadPolarClose cl, const HeadPolarStart st) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* const sXn = smem;                  // X   : row r, K = column
   unsigned char* const sXt = smem + DH * ROWB;      // X^T : row c, K = row of X
@@ -46,13 +46,15 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
   const int wm = wave >> 1, wn = wave & 1;          // this wavefront's 64 x 64 block of every 128 x 128 product
   const int64_t hoff = (int64_t)h * DH * DH;
 
+  if (!st.M) {   // the start iterate is given as planes
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int idx = q * 256 + tid, row = idx >> 4, chunk = idx & 15;
-    *reinterpret_cast<uint4*>(sXn + loff(row, chunk)) = *reinterpret_cast<const uint4*>(Xn0 + hoff + row * DH + chunk * 8);
-    *reinterpret_cast<uint4*>(sXt + loff(row, chunk)) = *reinterpret_cast<const uint4*>(Xt0 + hoff + row * DH + chunk * 8);
+    for (int q = 0; q < 8; ++q) {
+      const int idx = q * 256 + tid, row = idx >> 4, chunk = idx & 15;
+      *reinterpret_cast<uint4*>(sXn + loff(row, chunk)) = *reinterpret_cast<const uint4*>(Xn0 + hoff + row * DH + chunk * 8);
+      *reinterpret_cast<uint4*>(sXt + loff(row, chunk)) = *reinterpret_cast<const uint4*>(Xt0 + hoff + row * DH + chunk * 8);
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   auto frag = [&](const unsigned char* base, int row, int kk) {
     return *reinterpret_cast<const f16x8*>(base + loff(row, 2 * kk + half));
@@ -131,6 +133,38 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
   };
 
   f32x16 acc[2][2], accT[2][2];
+  if (st.M) {
+    // The start of the update in this launch as well (what the packing pass does on the general path):
+    // X0 = (M + lambda tau R_prev) / alpha, tau = ||M||_F / sqrt(dh), alpha = ||M||_F (1 + lambda), with ||M||_F^2 summed from
+    // the partial sums the reduction of the token shares left (or given whole: nparts = 1); lambda = 0 stands for the
+    // limit at fp32 resolution, an empty M for R_prev itself.  Elements in the accumulators' layout, so that the two LDS
+    // operands are written exactly as after a step.
+    double f2 = 0.0;
+    for (int p = 0; p < st.nparts; ++p) f2 += st.fro2_parts[(int64_t)h * st.nparts + p];
+    if (tid == 0) {
+      st.fro2_out[h] = f2;
+      if (st.ldot) st.ldot[h] = st.L[h];   // the l1 term of the rows this update consumes, kept before the statistics restart
+    }
+    const double f = sqrt(f2);
+    const bool empty = !(f > 0.0);
+    const float lambda = fmaxf(st.lambda, 9.5367431640625e-07f);
+    const float tau = (float)(f / sqrt((double)DH));
+    const float inv_alpha = empty ? 1.0f : (float)(1.0 / (f * (1.0 + (double)lambda)));
+    const float cm = empty ? 0.0f : inv_alpha, cr = empty ? 1.0f : lambda * tau * inv_alpha;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = 64 * wm + 32 * i + 8 * (e >> 2) + 4 * half + (e & 3), n = 64 * wn + 32 * j + col;
+          const int64_t off = hoff + (int64_t)m * DH + n;
+          acc[i][j][e] = cm * st.M[off] + cr * st.R[off];
+        }
+    store_transposed(sXt, 64 * wm, 64 * wn, acc, 0.0f, 1.0f);
+    store_natural(sXn, acc);
+    __syncthreads();
+  }
   for (int k = 0; k < sched.nsteps; ++k) {
     const bool last = k + 1 == sched.nsteps;
     // G = X^T X;  W = a I + b G (G symmetric: storing the transpose stores W itself)
@@ -349,9 +383,13 @@ __global__ void __launch_bounds__(256) k_head_polar128(const bf16_bits* __restri
 }  // namespace
 
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
-                                bf16_bits* Pn, bf16_bits* Pt, const HeadPolarClose* close, hipStream_t s) {
+                                bf16_bits* Pn, bf16_bits* Pt, const HeadPolarClose* close, const HeadPolarStart* start,
+                                hipStream_t s) {
   if (heads < 1 || sched.nsteps < 1 || sched.nsteps > kPolarScheduleMax) return hipErrorInvalidValue;
   if (close && (!close->R || !close->RopT || !close->M || !close->res_out || !close->sq_out || !close->inner_out)) return hipErrorInvalidValue;
+  if (start && (!start->M || !start->R || !start->fro2_parts || start->nparts < 1 || !start->fro2_out || (start->ldot && !start->L)))
+    return hipErrorInvalidValue;
+  if (!start && (!Xn0 || !Xt0)) return hipErrorInvalidValue;
   static PerDeviceOnce configured;
   hipError_t e = configured.run([] {
     hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(k_head_polar128<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -362,10 +400,11 @@ hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int 
     return r;
   });
   if (e != hipSuccess) return e;
+  const HeadPolarStart st = start ? *start : HeadPolarStart{};
   if (close)
-    hipLaunchKernelGGL(k_head_polar128<true>, dim3(heads), dim3(256), kSmemBytesClose, s, Xn0, Xt0, sched, X32, Pn, Pt, *close);
+    hipLaunchKernelGGL(k_head_polar128<true>, dim3(heads), dim3(256), kSmemBytesClose, s, Xn0, Xt0, sched, X32, Pn, Pt, *close, st);
   else
-    hipLaunchKernelGGL(k_head_polar128<false>, dim3(heads), dim3(256), kSmemBytes, s, Xn0, Xt0, sched, X32, Pn, Pt, HeadPolarClose{});
+    hipLaunchKernelGGL(k_head_polar128<false>, dim3(heads), dim3(256), kSmemBytes, s, Xn0, Xt0, sched, X32, Pn, Pt, HeadPolarClose{}, st);
   return hipGetLastError();
 }
 

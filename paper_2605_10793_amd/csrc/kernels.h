@@ -95,8 +95,22 @@ struct HeadPolarClose {
   double* inner_out;
   float res_max;
 };
+// start non-null: the launch forms the start iterate itself, X0 = (M + lambda tau R) / alpha per head (Xn0 / Xt0 unused,
+// may be null), from M, R (fp32 [heads][128][128]) and ||M_h||_F^2 = the sum of nparts partial sums per head
+// (fro2_parts[h * nparts + p]); it also stores that sum to fro2_out[h] and, if ldot is non-null, copies L[h] to ldot[h].
+struct HeadPolarStart {
+  const float* M;
+  const float* R;
+  const double* fro2_parts;
+  int nparts;
+  double* fro2_out;
+  float lambda;
+  const double* L;
+  double* ldot;
+};
 hipError_t launch_head_polar128(const bf16_bits* Xn0, const bf16_bits* Xt0, int heads, const PolarSchedule& sched, float* X32,
-                                bf16_bits* Pn, bf16_bits* Pt, const HeadPolarClose* close, hipStream_t s);
+                                bf16_bits* Pn, bf16_bits* Pt, const HeadPolarClose* close, const HeadPolarStart* start,
+                                hipStream_t s);
 
 // Per-row fake-quantisation error of Y [T][ld] (bf16 or fp32) into row_sse / row_en, then their sums over rows:
 // out[0] = SSE, out[1] = energy (skipped if out is null).  zero_point = 0: symmetric quantiser; 1: zero-point quantiser on [clip*min, clip*max].
