@@ -105,7 +105,8 @@ def compare_update(B, cal, oc, w, tag, check_R):
         # the multiply-add work the update reports as issued: of the order of the algorithmic 4 dh^3 per iteration and head
         # (below it where symmetric products run half their tiles, above it for padded tiles and split-plane products)
         algorithmic = 4.0 * w.dh ** 3 * w.heads * st_g[h]["iters"]
-        assert 0.5 * algorithmic <= st_g[h]["mfma_flop"] <= 16.0 * algorithmic, (tag, st_g[h]["mfma_flop"], algorithmic)
+        padded = -(-w.dh // 64) * 64 / w.dh          # the smallest tile is 64 x 64: narrow heads run padded tiles
+        assert 0.5 * algorithmic <= st_g[h]["mfma_flop"] <= 8.0 * padded ** 2 * algorithmic, (tag, st_g[h]["mfma_flop"], algorithmic)
         if check_R:
             dR = np.abs(Rg[h] - oc.R[h]).max()
             say(f"  {tag} head {h}: max|R - R_oracle| = {dR:.2e}")
@@ -173,7 +174,8 @@ def compare_quant(B, cal, oc, X, w, tag):
         near = diff <= 4 * ulp * (np.abs(Qo) + step[:, None]) + 1e-30
         assert np.all(diff <= step[:, None] * (1 + 2.0 ** -6) + 2 * ulp * np.abs(Qo) + 1e-30), tag   # + the levels' own rounding
         say(f"  {tag}: fake-quant zp={zp} clip={clip}: {100 * (1 - near.mean()):.4f} % of the entries on a neighbouring level")
-        assert near.mean() >= (0.997 if w.dtype == "bf16" else 0.9995), tag
+        # (a handful of rows: one such entry may be more than the fraction allows)
+        assert (~near).sum() <= max(2, (0.003 if w.dtype == "bf16" else 0.0005) * near.size), tag
         assert len(np.unique(Qg[0])) <= (16 if zp else 15)
         assert not Qbuf[:, w.d:].any()
         # the squared error of the emitted rows is the one the error entry points report
