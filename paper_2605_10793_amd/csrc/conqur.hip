@@ -85,6 +85,8 @@ struct conqur_ctx {
   // heads of width 128 with bf16 activations take the fused step kernel (head_step.hip)
   bool head_fused = false;
   float* Mpart = nullptr;                            // [head_splits][heads][128][128] partial M of the token shares
+  int ksplit_max = 0;                                // > 0: one narrow rotation (general path): the accumulate GEMM may split its
+                                                     // token range into up to this many shares of Mpart ([ksplit_max][dh][dh])
   int head_splits = 0;
   int parts_pending = 0;                             // > 0: M of all heads still lies in that many token shares of Mpart
                                                      // (a first batch's shares are summed when M is next needed: by the
@@ -280,6 +282,14 @@ conqur_status conqur_init(const conqur_config* cfg, const float* R0_host, conqur
     ctx->head_splits = head_step_splits(ctx->heads, ctx->tmax);
     A(dev_alloc(ctx, &ctx->Mpart, (size_t)ctx->head_splits * blk));
   }
+  // One rotation of a width whose dh x dh output gives the accumulate GEMM only a few tiles (dh <= 512: at most 64 of the
+  // chip's 256 compute units, each with the whole token range to itself): the token range is split into shares instead.
+  if (!ctx->head_fused && ctx->heads == 1 && dh <= 512 && (blk & 1023) == 0) {
+    const int tiles = gemm_num_workgroups((int)dh, (int)dh, 1);
+    ctx->ksplit_max = std::max(1, std::min(16, 256 / std::max(tiles, 1)));
+    if (ctx->ksplit_max > 1) A(dev_alloc(ctx, &ctx->Mpart, (size_t)ctx->ksplit_max * blk));
+    else ctx->ksplit_max = 0;
+  }
   A(dev_alloc(ctx, &ctx->dot_part, (size_t)ctx->heads * pack_dot_partials(ctx->dh)));
   for (int k = 0; k < 2; ++k) A(dev_alloc(ctx, &ctx->clk[k], (size_t)4 * kClkMaxWorkgroups));
   for (int s = 0; s < ST_COUNT && e == hipSuccess; ++s)
@@ -468,10 +478,24 @@ static conqur_status step_general(conqur_ctx* ctx, const void* X, int64_t T, int
     g.accumulate = ctx->m_empty ? 0 : 1;
     g.out_scale = 1.0f / (kXhatScale * std::sqrt((float)ctx->dh));   // the operand carries kXhatScale x^, the corner 1/sqrt(dh)
     g.ab_f16 = ctx->f32 ? 0 : 1;
-    const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
-    ctx->clk_wg[1] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
-    g.clk = ctx->clk_wg[1] ? ctx->clk[1] : nullptr;
-    HIP_TRY(launch_gemm_nt(g, EPI_F32, ctx->heads, s));
+    // shares of the token range: the largest count up to ksplit_max that divides the range into whole 64-token steps
+    int shares = 1;
+    for (int c = ctx->ksplit_max; c > 1; --c)
+      if ((Tk / 64) % c == 0) { shares = c; break; }
+    if (shares > 1) {
+      // every share is a batch entry: the operands advance along the tokens, the results go to the shares of Mpart
+      g.K = (int)(Tk / shares);
+      g.batchA = g.K; g.batchB = g.K;
+      g.C = ctx->Mpart; g.accumulate = 0;
+      ctx->clk_wg[1] = 0;
+      HIP_TRY(launch_gemm_nt(g, EPI_F32, shares, s));
+      HIP_TRY(launch_sum_shares(ctx->Mpart, shares, (int64_t)ctx->dh * ctx->dh, ctx->M, ctx->m_empty ? 0 : 1, s));
+    } else {
+      const int wg = gemm_num_workgroups(g.M, g.N, ctx->heads);
+      ctx->clk_wg[1] = (ctx->timing >= 2 && wg <= kClkMaxWorkgroups) ? wg : 0;
+      g.clk = ctx->clk_wg[1] ? ctx->clk[1] : nullptr;
+      HIP_TRY(launch_gemm_nt(g, EPI_F32, ctx->heads, s));
+    }
   }
   // no statistics kernel: the row counters were taken with the norms, and the l1 term of the accumulated rows is
   // sqrt(dh) <R_op, M> (k_dot_rm), evaluated when asked for and at the start of the update.

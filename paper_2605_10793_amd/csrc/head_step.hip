@@ -296,6 +296,13 @@ hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, in
   return hipGetLastError();
 }
 
+hipError_t launch_sum_shares(const float* part, int nsplit, int64_t n_total, float* M, int accumulate, hipStream_t s) {
+  if (nsplit < 1 || n_total < 1024 || (n_total & 1023)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_head_reduce<false>, dim3((unsigned)(n_total / 1024)), dim3(256), 0, s, part, nsplit, n_total, M, accumulate,
+                     (double*)nullptr);
+  return hipGetLastError();
+}
+
 hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, double* fro2_part, hipStream_t s) {
   const int64_t n_total = (int64_t)heads * DH * DH;
   const dim3 grid((unsigned)(n_total / 1024));

@@ -69,6 +69,8 @@ hipError_t launch_head_step128(const bf16_bits* X, int64_t T, int64_t stride, in
                                unsigned long long* skipped, int* nonfinite, bf16_bits* St, int64_t pitch, hipStream_t s);
 // fro2_part non-null: also 16 partial sums of squares per head of the resulting M (kHeadReduceParts doubles per head, in
 // head order), whose sum per head is ||M_h||_F^2.
+// The same sum for any matrix of n_total floats (a multiple of 1024) held as nsplit shares [nsplit][n_total], fixed order.
+hipError_t launch_sum_shares(const float* part, int nsplit, int64_t n_total, float* M, int accumulate, hipStream_t s);
 constexpr int kHeadReduceParts = 16;
 hipError_t launch_head_reduce(const float* Mpart, int nsplit, int heads, float* M, int accumulate, double* fro2_part, hipStream_t s);
 

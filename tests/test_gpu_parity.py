@@ -181,7 +181,10 @@ def compare_quant(B, cal, oc, X, w, tag):
         # the squared error of the emitted rows is the one the error entry points report
         sg = (cal.quant_error_zp(Xd, 4, clip) if zp else cal.quant_error(Xd, 4))[0]
         sse_rows = ((Qbuf[:, :w.d].double() - Ybuf[:, :w.d].double()) ** 2).sum(1).cpu().numpy()[rows_ok].sum()
-        assert abs(sse_rows - sg) <= (2e-2 if w.dtype == "bf16" else 1e-4) * sg + 1e-30, (tag, sse_rows, sg)
+        # (bf16: the emitted levels are rounded once more; with rows of a few dozen entries that rounding, which sits on
+        # the few large entries of a row, does not average out as it does over wide rows)
+        tol_rows = (2e-2 if w.d >= 64 else 6e-2) if w.dtype == "bf16" else 1e-4
+        assert abs(sse_rows - sg) <= tol_rows * sg + 1e-30, (tag, sse_rows, sg)
 
 
 def run_stream(B, w, n_batches, check_R, tokens=None, R0=None, **cal_kwargs):
