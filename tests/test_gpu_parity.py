@@ -682,6 +682,46 @@ def test_rows_with_a_pitch_wider_than_d(B, d, heads, dtype):
         cal.close()
 
 
+@pytest.mark.parametrize("d,heads", [(256, 1), (256, 2), (384, 3)])
+def test_update_whose_start_cancels_is_nudged_towards_the_previous_rotation(B, d, heads):
+    """A head whose M is exactly -beta R_prev under prox_lambda = 1: M + lambda tau R_prev cancels to rounding noise, every
+    singular value of the start iterate lies far below the bound the schedule assumes, and the main phase leaves them
+    near zero.  The update must notice (residual near sqrt(dh)), nudge the iterate towards R_prev and finish there:
+    every orthogonal matrix maximises <R, 0>, and the one nearest R_prev is R_prev.  The other heads carry an ordinary
+    M and must come out as the oracle's; with heads of width 128 they take their closing step inside the main phase's
+    launch while the cancelled head declines it, so the general closing steps and the nudge run after that launch."""
+    dh = d // heads
+    w = I.small_workload(d, 300, n_batches=1, heads=heads, dtype="bf16", seed=4242 + d + heads, prox_lambda=1.0)
+    R0 = I.initial_rotation(w)
+    oc = O.OracleCalibrator(d, heads, "bf16", R0, 1.0)
+    oc.step_batch(I.batch(w, 0))
+    M = oc.M.astype(np.float32)
+    bad = heads - 1
+    M[bad] = -0.125 * R0[bad]                    # exact in fp32
+    oc.M[...] = M.astype(np.float64)
+    cal = B.Calibrator(d, heads, "bf16", R0, max_tokens=300, prox_lambda=1.0)
+    try:
+        cal.set_state(R=R0, M=M)
+        R_prev = oc.R.copy()
+        st_o = oc.update_rotation()
+        rc, st_g = cal.update_rotation()
+        Rg, _, _ = cal.get_state(want_M=False)
+        for h in range(heads):
+            R64 = Rg[h].astype(np.float64)
+            orth = np.linalg.norm(R64.T @ R64 - np.eye(dh))
+            say(f"  cancelled start, head {h}: iters={st_g[h]['iters']} orth={orth:.2e} max|R - R_prev|={np.abs(R64 - R_prev[h]).max():.2e}")
+            assert orth <= TOL_ORTH, (h, orth)
+            if h == bad:
+                assert np.abs(R64 - R_prev[h]).max() <= 1e-2, h
+            else:
+                A = M[h].astype(np.float64) + st_o[h]["tau"] * R_prev[h].astype(np.float64)
+                best = float((oc.R[h].astype(np.float64) * A).sum())
+                got = float((R64 * A).sum())
+                assert abs(got - best) <= TOL_REL * abs(best), (h, got, best)
+    finally:
+        cal.close()
+
+
 def test_pooled_batches_before_one_update(B):
     """Alg. 1 pools several sites into one update: three step_batch calls (shrinking T), one update."""
     w = I.small_workload(256, 384, n_batches=3, seed=77, prox_lambda=0.0)
