@@ -866,6 +866,18 @@ def test_error_paths(B):
         assert rc == B.ENOCONV and st[0]["orth_err"] > 1e-4
     finally:
         cal.close()
+    # the same cap on heads of width 128 (one launch for start, main phase and closing step): with 1 or 2 iterations
+    # allowed the closing step has no room, the residual is measured and the cap reported; R is replaced all the same
+    for cap in (1, 2):
+        w = I.small_workload(256, 200, heads=2, seed=5, prox_lambda=0.1)
+        cal = B.Calibrator(256, 2, "bf16", I.initial_rotation(w), max_tokens=200, prox_lambda=0.1, polar_max_iters=cap)
+        try:
+            cal.step_batch(B.to_device(I.batch(w, 0), "bf16"))
+            rc, st = cal.update_rotation(allow=(B.ENOCONV,))
+            assert rc == B.ENOCONV and st[0]["iters"] <= cap and st[0]["orth_err"] > 1e-4, (cap, rc, st[0])
+            assert np.isfinite(cal.get_state(want_M=False)[0]).all()
+        finally:
+            cal.close()
 
 
 def test_quant_error_closed_forms(B):
